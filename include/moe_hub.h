@@ -1,0 +1,157 @@
+/*
+ * moe_hub.h - C ABI of the MI355X (gfx950) MoE-layer hot path.
+ *
+ * One GPU's share of an expert-parallel MoE layer, following the five steps of
+ * the paper's Section II-A (routing, dispatch, expert computation, combine,
+ * scaling).  The dispatch step is split the way Section III-A describes the
+ * software "mediation" that precedes any transfer: first the destination
+ * address of every routed row is resolved (moe_dispatch_layout), then rows are
+ * moved into dense, send-ready regions (moe_permute).
+ *
+ * Conventions shared by every call
+ *  - All data pointers are DEVICE pointers owned by the caller.  The library
+ *    never allocates, frees or copies to the host, and never synchronises: a
+ *    call enqueues kernels on `stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream) and returns.  Segment offsets and counts stay on the
+ *    device between calls; no step needs them on the host.
+ *  - Matrices are row-major and dense.  A row is one token (Section IV-A);
+ *    rows must be 16-byte aligned: base pointers 16-byte aligned and
+ *    H * sizeof(element) (and F * sizeof(element)) a multiple of 16.
+ *  - dtype is the storage type of activations and expert weights: MOE_BF16
+ *    (fp32 accumulation) or MOE_F32.  Router weights and logits are fp32.
+ *  - Return value: MOE_OK, or a negative error.  On error nothing has been
+ *    launched and no output was touched; moe_last_error() describes it.
+ *  - N == 0 (or M == 0) is a successful no-op.  Inputs must be finite.
+ *  - No global mutable state: calls on different streams/threads are
+ *    independent as long as their buffers are.
+ */
+#ifndef MOE_HUB_H
+#define MOE_HUB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MOE_OK = 0,
+    MOE_ERR_ARG = -1,         /* null pointer, size out of range, misaligned row */
+    MOE_ERR_UNSUPPORTED = -2, /* valid but not built (dtype, E too large, ...)    */
+    MOE_ERR_WORKSPACE = -3,   /* workspace missing or smaller than required       */
+    MOE_ERR_LAUNCH = -4       /* the HIP runtime refused a launch                 */
+};
+
+enum { MOE_BF16 = 0, MOE_F32 = 1 };
+
+enum {
+    MOE_SCORE_SOFTMAX_TOPK = 0, /* softmax over the K selected logits               */
+    MOE_SCORE_SIGMOID_TOPK = 1  /* sigmoid of each selected logit, divided by their sum */
+};
+
+enum { MOE_OP_ROUTE = 0, MOE_OP_DISPATCH_LAYOUT = 1, MOE_OP_GROUPED_FFN = 2 };
+
+enum { MOE_MAX_EXPERTS = 1024, MOE_MAX_TOPK = 32 };
+
+/* Text of the last error raised on the calling thread ("" if none). */
+const char *moe_last_error(void);
+
+/* Bytes of device workspace `op` needs for these sizes (arguments an op does not
+ * use are ignored).  ROUTE: N*E fp32 logits (only when logits_opt is NULL).
+ * DISPATCH_LAYOUT: per-chunk expert histograms.  GROUPED_FFN: the activation
+ * a[M,F] between the two GEMMs plus the tile schedule.  Returns 0 on bad sizes. */
+size_t moe_workspace_bytes(int op, int64_t N, int64_t H, int E, int K, int G, int64_t F, int dtype);
+
+/*
+ * Routing (Section II-A, step 1): gating scores, top-K selection, normalisation.
+ *
+ *   logit[n,e] = sum_h x[n,h] * W_r[h,e]  (+ bias[e] when bias != NULL)
+ * in fp32, in one fixed order so that the selection is reproducible bit for
+ * bit: 64 partial sums, partial l accumulates h = l, l+64, ... ascending with
+ * fused multiply-adds; the partials are then folded in six pairwise rounds
+ * s = 32,16,8,4,2,1 (p[l] += p[l^s]); the bias is added last.
+ * Selection is on the logits: the K largest per token, equal logits to the
+ * lower expert index; topk_idx[n,0..K) in descending preference.
+ * topk_w[n,k]: per score_mode, normalised over the K selected (sums to 1).
+ *
+ *   x        [N,H] dtype          W_r  [H,E] fp32        bias [E] fp32 or NULL
+ *   topk_idx [N,K] int32 (out)    topk_w [N,K] fp32 (out)
+ *   logits_opt [N,E] fp32 (out) or NULL; when NULL, ws must hold N*E floats.
+ * Requires 1 <= K <= min(E, MOE_MAX_TOPK), E <= MOE_MAX_EXPERTS.
+ */
+int moe_route(const void *x, int dtype, int64_t N, int64_t H,
+              const float *W_r, const float *bias, int E, int K, int score_mode,
+              int32_t *topk_idx, float *topk_w, float *logits_opt,
+              void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Address resolution (the mediation of Section III-A, kept on the GPU): how
+ * many rows each expert and each logical destination receives, where each
+ * region starts, and the slot of every routed row.  Regions are dense, sized
+ * by the counts, and laid out back to back in expert order; nothing is dropped
+ * or padded (Section IV-A: conservative regions, dense packing; the byte
+ * address of slot s is base + s * RowSize).  Expert e belongs to destination
+ * e / (E/G).  Inside a region rows keep ascending flat order r = n*K + k, so
+ * the result is the stable counting sort of topk_idx by expert and is unique.
+ *
+ *   topk_idx       [N*K] int32, values in [0,E)
+ *   expert_counts  [E]    expert_offsets [E+1]  (exclusive scan, [E] = N*K)
+ *   dest_counts    [G]    dest_offsets   [G+1]  (dest_offsets[g] = expert_offsets[g*E/G])
+ *   slot_of_row    [N*K]  slot of flat row r
+ *   row_of_slot    [N*K]  inverse map
+ * Requires E % G == 0, N*K < 2^31.  ws: moe_workspace_bytes(MOE_OP_DISPATCH_LAYOUT, ...).
+ * Out-of-range expert indices are a precondition violation (rows are then ignored).
+ */
+int moe_dispatch_layout(const int32_t *topk_idx, int64_t N, int K, int E, int G,
+                        int32_t *expert_counts, int32_t *expert_offsets,
+                        int32_t *dest_counts, int32_t *dest_offsets,
+                        int32_t *slot_of_row, int32_t *row_of_slot,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Dispatch, local half (Section II-A, step 2): xp[slot_of_row[n*K+k], :] = x[n, :],
+ * a bitwise copy of each token row into each of its K slots.  The result is
+ * expert-contiguous and therefore destination-contiguous: segment
+ * [dest_offsets[g], dest_offsets[g+1]) is what would be sent to destination g.
+ *   x [N,H] dtype     xp [N*K,H] dtype (out)
+ */
+int moe_permute(const void *x, int dtype, int64_t N, int64_t H, int K,
+                const int32_t *slot_of_row, const int32_t *row_of_slot,
+                void *xp, void *stream);
+
+/*
+ * Expert computation (Section II-A, step 3: two GEMMs with an activation in
+ * between), gated form, for E_local experts over the rows of xp:
+ *   rows [seg_offsets[e], seg_offsets[e+1]) belong to local expert e
+ *   g = xp_row W_gate[e]^T, u = xp_row W_up[e]^T, a = g/(1+exp(-g)) * u,
+ *   y_row = a W_down[e]^T
+ * Weights are stored "out x in" (the reduction index is contiguous):
+ *   W_gate, W_up [E_local,F,H]    W_down [E_local,H,F]    (dtype)
+ *   xp [M,H]   y [M,H] (out)   seg_offsets [E_local+1] int32 ON THE DEVICE,
+ *   non-decreasing, within [0,M].  Rows outside every segment are not written.
+ * bf16: fp32 accumulation, `a` and `y` rounded to bf16 (nearest even).
+ * ws: moe_workspace_bytes(MOE_OP_GROUPED_FFN, M, H, E_local, 0, 0, F, dtype).
+ * For an expert-parallel rank pass seg_offsets = expert_offsets + g*E/G and the
+ * weights of that destination's experts.
+ */
+int moe_grouped_ffn(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
+                    int E_local, const int32_t *seg_offsets,
+                    const void *W_gate, const void *W_up, const void *W_down,
+                    void *y, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Combine and scaling (Section II-A, steps 4-5): rows return to their tokens
+ * and are summed with the routing weights,
+ *   out[n,:] = sum_{k=0..K-1} topk_w[n,k] * y[slot_of_row[n*K+k], :]
+ * accumulated in fp32 in ascending k, rounded once to dtype.
+ *   y [N*K,H] dtype    topk_w [N,K] fp32    out [N,H] dtype (out)
+ */
+int moe_combine(const void *y, int dtype, int64_t N, int64_t H, int K,
+                const int32_t *slot_of_row, const float *topk_w,
+                void *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_HUB_H */

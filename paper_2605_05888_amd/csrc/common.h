@@ -1,0 +1,67 @@
+// Shared declarations of the HIP MoE-layer library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/moe_hub.h"
+
+namespace moe {
+
+// Records a message for moe_last_error() and returns `code`.
+int fail(int code, const char *fmt, ...);
+void clear_error();
+
+// Launch check: turns a pending HIP launch error into MOE_ERR_LAUNCH.
+int check_launch(const char *what);
+
+constexpr int kWave = 64;
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16)
+{
+    return __uint_as_float(bits16 << 16);
+}
+
+// Round-to-nearest-even fp32 -> bf16 bit pattern (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t b = __float_as_uint(f);
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- per-step launchers (each validates nothing: api.hip has done it) ----
+int launch_route(const void *x, int dtype, int64_t N, int64_t H, const float *W_r,
+                 const float *bias, int E, int K, int score_mode, int32_t *topk_idx,
+                 float *topk_w, float *logits, hipStream_t st);
+
+size_t layout_workspace_bytes(int64_t R, int E);
+int launch_layout(const int32_t *topk_idx, int64_t R, int E, int G, int32_t *expert_counts,
+                  int32_t *expert_offsets, int32_t *dest_counts, int32_t *dest_offsets,
+                  int32_t *slot_of_row, int32_t *row_of_slot, void *ws, hipStream_t st);
+
+int launch_permute(const void *x, int64_t row_bytes, int64_t N, int K,
+                   const int32_t *slot_of_row, void *xp, hipStream_t st);
+
+int launch_combine(const void *y, int dtype, int64_t N, int64_t H, int K,
+                   const int32_t *slot_of_row, const float *topk_w, void *out, hipStream_t st);
+
+size_t ffn_workspace_bytes(int64_t M, int64_t H, int64_t F, int E_local, int dtype);
+int launch_grouped_ffn(const void *xp, int dtype, int64_t M, int64_t H, int64_t F, int E_local,
+                       const int32_t *seg_offsets, const void *W_gate, const void *W_up,
+                       const void *W_down, void *y, void *ws, hipStream_t st);
+
+}  // namespace moe

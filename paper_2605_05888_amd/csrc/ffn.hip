@@ -1,0 +1,485 @@
+// Expert computation (Section II-A, step 3): grouped SwiGLU FFN over ragged,
+// expert-contiguous row segments whose offsets live on the device.
+//
+//   GEMM1  a[m, f] = silu(xp[m,:] . W_gate[e,f,:]) * (xp[m,:] . W_up[e,f,:])
+//   GEMM2  y[m, c] = a[m,:] . W_down[e,c,:]
+//
+// Both operands of both GEMMs have the reduction index contiguous, so every lane
+// fetches its matrix-core operand (8 consecutive bf16 of one row) with a single
+// 16-byte LDS read.  bf16 path: v_mfma_f32_32x32x16_bf16, fp32 accumulators,
+// LDS tiles double buffered with a 16-byte-chunk XOR swizzle, one barrier per
+// K tile.  GEMM1 keeps gate and up columns of the same f in one wavefront, so
+// the activation is applied to the accumulators and `g`, `u` never reach memory.
+//
+// Scheduling is device side: a small kernel turns seg_offsets into a tile table
+// (expert, first row, end row, column tile), ordered so that tiles that run
+// together share weight tiles; workgroup ids are spread so that each XCD's L2
+// sees a compact patch of that order.  Nothing about the routing result is read
+// on the host.
+#include "common.h"
+
+namespace moe {
+
+// ------------------------------------------------------------------------
+// tile table
+// ------------------------------------------------------------------------
+struct TileEntry {
+    int32_t expert; // local expert
+    int32_t m0;     // first row of the tile
+    int32_t m_end;  // end of the expert's segment (rows >= m_end are not written)
+    int32_t n_tile; // column tile
+};
+
+struct TileTableHeader {
+    int32_t num_tiles;
+    int32_t pad[3];
+};
+
+constexpr int kSchedThreads = 256;
+
+// table[L] for L in [0, num_tiles): order = expert, then column tile, then row tile.
+__global__ __launch_bounds__(kSchedThreads) void build_tile_table(
+    const int32_t *__restrict__ seg_offsets, int E_local, int64_t M, int BM, int n_tiles,
+    int max_tiles, TileTableHeader *__restrict__ hdr, TileEntry *__restrict__ table)
+{
+    __shared__ int32_t start[MOE_MAX_EXPERTS + 1]; // first tile of each expert
+    __shared__ int32_t wave_tot[kSchedThreads / kWave];
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    // exclusive scan of tiles per expert; thread owns a contiguous run of experts
+    const int per = (E_local + kSchedThreads - 1) / kSchedThreads;
+    const int e_lo = tid * per;
+    int32_t mine = 0;
+    for (int j = 0; j < per; ++j) {
+        int e = e_lo + j;
+        if (e < E_local) {
+            int64_t lo = seg_offsets[e], hi = seg_offsets[e + 1];
+            lo = lo < 0 ? 0 : (lo > M ? M : lo);
+            hi = hi < lo ? lo : (hi > M ? M : hi);
+            mine += (int32_t)((hi - lo + BM - 1) / BM) * n_tiles;
+        }
+    }
+    int32_t inc = mine;
+    for (int d = 1; d < kWave; d <<= 1) {
+        int32_t t = __shfl_up(inc, d);
+        if (lane >= d)
+            inc += t;
+    }
+    if (lane == kWave - 1)
+        wave_tot[wave] = inc;
+    __syncthreads();
+    int32_t base = 0;
+    for (int w = 0; w < wave; ++w)
+        base += wave_tot[w];
+    int32_t run = base + inc - mine;
+    for (int j = 0; j < per; ++j) {
+        int e = e_lo + j;
+        if (e < E_local) {
+            int64_t lo = seg_offsets[e], hi = seg_offsets[e + 1];
+            lo = lo < 0 ? 0 : (lo > M ? M : lo);
+            hi = hi < lo ? lo : (hi > M ? M : hi);
+            start[e] = run;
+            run += (int32_t)((hi - lo + BM - 1) / BM) * n_tiles;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        // total = start[last] + tiles(last)
+        int e = E_local - 1;
+        int64_t lo = seg_offsets[e], hi = seg_offsets[e + 1];
+        lo = lo < 0 ? 0 : (lo > M ? M : lo);
+        hi = hi < lo ? lo : (hi > M ? M : hi);
+        start[E_local] = start[e] + (int32_t)((hi - lo + BM - 1) / BM) * n_tiles;
+    }
+    __syncthreads();
+    int32_t total = start[E_local];
+    if (total > max_tiles)
+        total = max_tiles; // cannot happen for monotone offsets within [0, M]
+    if (blockIdx.x == 0 && tid == 0)
+        hdr->num_tiles = total;
+    for (int L = blockIdx.x * kSchedThreads + tid; L < total; L += gridDim.x * kSchedThreads) {
+        int lo_e = 0, hi_e = E_local; // last e with start[e] <= L
+        while (hi_e - lo_e > 1) {
+            int mid = (lo_e + hi_e) >> 1;
+            if (start[mid] <= L)
+                lo_e = mid;
+            else
+                hi_e = mid;
+        }
+        const int e = lo_e;
+        int64_t lo = seg_offsets[e], hi = seg_offsets[e + 1];
+        lo = lo < 0 ? 0 : (lo > M ? M : lo);
+        hi = hi < lo ? lo : (hi > M ? M : hi);
+        const int m_tiles = (int)((hi - lo + BM - 1) / BM);
+        const int local = L - start[e];
+        TileEntry t;
+        t.expert = e;
+        t.n_tile = local / m_tiles;
+        t.m0 = (int32_t)lo + (local % m_tiles) * BM;
+        t.m_end = (int32_t)hi;
+        table[L] = t;
+    }
+}
+
+// ------------------------------------------------------------------------
+// bf16 matrix-core grouped GEMM
+// ------------------------------------------------------------------------
+constexpr int kXcds = 8;
+
+// Workgroup id -> position in the tile order.  Ids are dealt round-robin to the
+// 8 XCDs; each XCD takes runs of kPatch consecutive tiles so its L2 sees tiles
+// that share weight and activation rows.
+__device__ __forceinline__ int tile_of_workgroup(int id, int kPatch)
+{
+    const int xcd = id % kXcds, j = id / kXcds;
+    return (j / kPatch) * (kPatch * kXcds) + xcd * kPatch + (j % kPatch);
+}
+
+__device__ __forceinline__ float silu_mul(float g, float u)
+{
+    return g / (1.0f + __expf(-g)) * u;
+}
+
+template <int BM, int BN, int BK, int WM, int WN, bool kSwiglu>
+struct GemmCfg {
+    static constexpr int kThreads = WM * WN * kWave;
+    static constexpr int kWaveM = BM / WM;     // rows per wavefront
+    static constexpr int kWaveN = BN / WN;     // LDS B rows per wavefront
+    static constexpr int kBlkM = kWaveM / 32;  // 32x32 blocks per wavefront, M
+    static constexpr int kBlkN = kWaveN / 32;
+    static constexpr int kChunksPerRow = BK / 8; // 16-byte chunks per tile row
+    static constexpr int kAChunks = BM * kChunksPerRow / kThreads; // per thread
+    static constexpr int kBChunks = BN * kChunksPerRow / kThreads;
+    static constexpr int kOutCols = kSwiglu ? BN / 2 : BN; // output columns per tile
+    static constexpr size_t kLdsBytes = 2 * (size_t)(BM + BN) * BK * 2;
+    static_assert(kChunksPerRow == 8, "swizzle assumes 128-byte tile rows");
+    static_assert(kWaveM % 32 == 0 && kWaveN % 32 == 0, "wave tile must be 32x32 blocks");
+    static_assert(!kSwiglu || kBlkN % 2 == 0, "gate and up halves");
+};
+
+// byte offset of 16-byte chunk `c` of tile row `r` (rows are 128 bytes)
+__device__ __forceinline__ int lds_chunk_off(int r, int c) { return r * 128 + ((c ^ (r & 7)) << 4); }
+
+template <int BM, int BN, int BK, int WM, int WN, bool kSwiglu>
+__global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
+    const uint16_t *__restrict__ A, int64_t M, int Kdim, int Ndim,
+    const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
+    uint16_t *__restrict__ C, const TileTableHeader *__restrict__ hdr,
+    const TileEntry *__restrict__ table, int patch)
+{
+    using Cfg = GemmCfg<BM, BN, BK, WM, WN, kSwiglu>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int L = tile_of_workgroup(blockIdx.x, patch);
+    if (L >= hdr->num_tiles)
+        return;
+    const TileEntry te = table[L];
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const int wm = wave / WN, wn = wave % WN;
+
+    constexpr int kStageBytes = (BM + BN) * BK * 2, kATileBytes = BM * BK * 2;
+    auto ldsA = [&](int buf) { return lds + buf * kStageBytes; };
+    auto ldsB = [&](int buf) { return lds + buf * kStageBytes + kATileBytes; };
+
+    // ---- global source pointers of this thread's chunks (advance by BK per K tile)
+    const uint16_t *a_src[Cfg::kAChunks];
+    int a_dst[Cfg::kAChunks];
+#pragma unroll
+    for (int i = 0; i < Cfg::kAChunks; ++i) {
+        const int q = tid + i * Cfg::kThreads;
+        const int r = q / 8, c = q % 8;
+        int64_t m = (int64_t)te.m0 + r;
+        if (m >= te.m_end)
+            m = te.m_end - 1; // rows past the segment repeat its last row; never stored
+        a_src[i] = A + m * Kdim + c * 8;
+        a_dst[i] = lds_chunk_off(r, c);
+    }
+    const uint16_t *b_src[Cfg::kBChunks];
+    int b_dst[Cfg::kBChunks];
+    const int n0 = te.n_tile * Cfg::kOutCols;
+#pragma unroll
+    for (int i = 0; i < Cfg::kBChunks; ++i) {
+        const int q = tid + i * Cfg::kThreads;
+        const int r = q / 8, c = q % 8;
+        const uint16_t *base = B0;
+        int col;
+        if (kSwiglu) {
+            // LDS B rows of one wavefront: first half gate columns, second half the same up columns
+            const int w = r / Cfg::kWaveN, jj = r % Cfg::kWaveN, half = Cfg::kWaveN / 2;
+            base = (jj < half) ? B0 : B1;
+            col = n0 + w * half + (jj % half);
+        } else {
+            col = n0 + r;
+        }
+        if (col >= Ndim)
+            col = Ndim - 1;
+        b_src[i] = base + ((int64_t)te.expert * Ndim + col) * Kdim + c * 8;
+        b_dst[i] = lds_chunk_off(r, c);
+    }
+
+    f32x16 acc[Cfg::kBlkM][Cfg::kBlkN];
+#pragma unroll
+    for (int i = 0; i < Cfg::kBlkM; ++i)
+#pragma unroll
+        for (int j = 0; j < Cfg::kBlkN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[i][j][r] = 0.0f;
+
+    u32x4 a_stage[Cfg::kAChunks], b_stage[Cfg::kBChunks];
+    const int KT = Kdim / BK;
+
+    auto load_global = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < Cfg::kAChunks; ++i)
+            a_stage[i] = *reinterpret_cast<const u32x4 *>(a_src[i] + (int64_t)kt * BK);
+#pragma unroll
+        for (int i = 0; i < Cfg::kBChunks; ++i)
+            b_stage[i] = *reinterpret_cast<const u32x4 *>(b_src[i] + (int64_t)kt * BK);
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < Cfg::kAChunks; ++i)
+            *reinterpret_cast<u32x4 *>(ldsA(buf) + a_dst[i]) = a_stage[i];
+#pragma unroll
+        for (int i = 0; i < Cfg::kBChunks; ++i)
+            *reinterpret_cast<u32x4 *>(ldsB(buf) + b_dst[i]) = b_stage[i];
+    };
+
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+
+    const int frag_row = lane % 32, frag_kg = lane / 32;
+    for (int kt = 0; kt < KT; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < KT)
+            load_global(kt + 1);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 af[Cfg::kBlkM], bfr[Cfg::kBlkN];
+#pragma unroll
+            for (int i = 0; i < Cfg::kBlkM; ++i) {
+                const int r = wm * Cfg::kWaveM + i * 32 + frag_row;
+                af[i] = *reinterpret_cast<const bf16x8 *>(ldsA(buf) + lds_chunk_off(r, ks * 2 + frag_kg));
+            }
+#pragma unroll
+            for (int j = 0; j < Cfg::kBlkN; ++j) {
+                const int r = wn * Cfg::kWaveN + j * 32 + frag_row;
+                bfr[j] = *reinterpret_cast<const bf16x8 *>(ldsB(buf) + lds_chunk_off(r, ks * 2 + frag_kg));
+            }
+#pragma unroll
+            for (int i = 0; i < Cfg::kBlkM; ++i)
+#pragma unroll
+                for (int j = 0; j < Cfg::kBlkN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < KT)
+            store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: accumulator element (i-block, j-block, reg r) is
+    //      row = 8*(r/4) + 4*(lane/32) + r%4, col = lane%32 of its 32x32 block
+    const int col_in_blk = lane % 32, row_base = (lane / 32) * 4;
+    if (kSwiglu) {
+        constexpr int kHalfBlk = Cfg::kBlkN / 2;
+#pragma unroll
+        for (int i = 0; i < Cfg::kBlkM; ++i)
+#pragma unroll
+            for (int j = 0; j < kHalfBlk; ++j) {
+                const int col = n0 + wn * (Cfg::kWaveN / 2) + j * 32 + col_in_blk;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t m = (int64_t)te.m0 + wm * Cfg::kWaveM + i * 32 + (r / 4) * 8 + row_base + (r % 4);
+                    if (m < te.m_end && col < Ndim)
+                        C[m * Ndim + col] = (uint16_t)f32_to_bf16_bits(silu_mul(acc[i][j][r], acc[i][j + kHalfBlk][r]));
+                }
+            }
+    } else {
+#pragma unroll
+        for (int i = 0; i < Cfg::kBlkM; ++i)
+#pragma unroll
+            for (int j = 0; j < Cfg::kBlkN; ++j) {
+                const int col = n0 + wn * Cfg::kWaveN + j * 32 + col_in_blk;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int64_t m = (int64_t)te.m0 + wm * Cfg::kWaveM + i * 32 + (r / 4) * 8 + row_base + (r % 4);
+                    if (m < te.m_end && col < Ndim)
+                        C[m * Ndim + col] = (uint16_t)f32_to_bf16_bits(acc[i][j][r]);
+                }
+            }
+    }
+}
+
+// ------------------------------------------------------------------------
+// fp32 path (small, correctness-oriented): one thread per output element
+// ------------------------------------------------------------------------
+__device__ __forceinline__ int expert_of_row(const int32_t *seg, int E_local, int64_t m)
+{
+    int lo = 0, hi = E_local; // last e with seg[e] <= m
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (seg[mid] <= m)
+            lo = mid;
+        else
+            hi = mid;
+    }
+    return (m >= seg[lo] && m < seg[lo + 1]) ? lo : -1;
+}
+
+__global__ __launch_bounds__(256) void ffn_f32_gate_up(const float *__restrict__ xp, int64_t M, int H,
+                                                     int F, int E_local,
+                                                     const int32_t *__restrict__ seg,
+                                                     const float *__restrict__ Wg,
+                                                     const float *__restrict__ Wu,
+                                                     float *__restrict__ a)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= M * F)
+        return;
+    const int64_t m = i / F;
+    const int f = (int)(i % F);
+    const int e = expert_of_row(seg, E_local, m);
+    if (e < 0)
+        return;
+    const float *xr = xp + m * H;
+    const float *g = Wg + ((int64_t)e * F + f) * H;
+    const float *u = Wu + ((int64_t)e * F + f) * H;
+    float sg = 0.0f, su = 0.0f;
+    for (int h = 0; h < H; ++h) {
+        sg = fmaf(xr[h], g[h], sg);
+        su = fmaf(xr[h], u[h], su);
+    }
+    a[i] = sg / (1.0f + expf(-sg)) * su;
+}
+
+__global__ __launch_bounds__(256) void ffn_f32_down(const float *__restrict__ a, int64_t M, int H, int F,
+                                                  int E_local, const int32_t *__restrict__ seg,
+                                                  const float *__restrict__ Wd, float *__restrict__ y)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= M * H)
+        return;
+    const int64_t m = i / H;
+    const int c = (int)(i % H);
+    const int e = expert_of_row(seg, E_local, m);
+    if (e < 0)
+        return;
+    const float *ar = a + m * F;
+    const float *w = Wd + ((int64_t)e * H + c) * F;
+    float s = 0.0f;
+    for (int f = 0; f < F; ++f)
+        s = fmaf(ar[f], w[f], s);
+    y[i] = s;
+}
+
+// ------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------
+struct FfnPlan {
+    bool big;
+    int BM, out_cols1, out_cols2;
+    int n_tiles1, n_tiles2, max_m_tiles;
+    size_t off_a, off_hdr1, off_tab1, off_hdr2, off_tab2, total;
+};
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static FfnPlan make_plan(int64_t M, int64_t H, int64_t F, int E_local)
+{
+    FfnPlan p;
+    p.big = (M / (E_local > 0 ? E_local : 1)) >= 192;
+    p.BM = p.big ? 256 : 128;
+    p.out_cols1 = p.big ? 128 : 64; // GEMM1 writes BN/2 columns of `a` per tile
+    p.out_cols2 = p.big ? 256 : 128;
+    p.n_tiles1 = (int)ceil_div(F, p.out_cols1);
+    p.n_tiles2 = (int)ceil_div(H, p.out_cols2);
+    p.max_m_tiles = (int)(M / p.BM) + E_local;
+    size_t o = 0;
+    p.off_a = o;
+    o = align_up(o + (size_t)M * F * 2, 256);
+    p.off_hdr1 = o;
+    o += 256;
+    p.off_tab1 = o;
+    o = align_up(o + (size_t)p.max_m_tiles * p.n_tiles1 * sizeof(TileEntry), 256);
+    p.off_hdr2 = o;
+    o += 256;
+    p.off_tab2 = o;
+    o = align_up(o + (size_t)p.max_m_tiles * p.n_tiles2 * sizeof(TileEntry), 256);
+    p.total = o;
+    return p;
+}
+
+size_t ffn_workspace_bytes(int64_t M, int64_t H, int64_t F, int E_local, int dtype)
+{
+    if (dtype == MOE_F32)
+        return align_up((size_t)M * F * 4, 256);
+    return make_plan(M, H, F, E_local).total;
+}
+
+template <int BM, int BN, int BK, int WM, int WN, bool kSwiglu>
+static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const uint16_t *B0,
+                        const uint16_t *B1, uint16_t *C, const TileTableHeader *hdr,
+                        const TileEntry *table, int max_tiles, int patch, hipStream_t st)
+{
+    using Cfg = GemmCfg<BM, BN, BK, WM, WN, kSwiglu>;
+    auto kern = grouped_gemm_bf16<BM, BN, BK, WM, WN, kSwiglu>;
+    static bool attr_set = false; // raising the dynamic LDS limit is idempotent
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::kLdsBytes);
+        attr_set = true;
+    }
+    // grid covers the worst-case tile count, rounded up to whole patches over all XCDs
+    const int group = patch * kXcds;
+    const int grid = (int)ceil_div(max_tiles, group) * group;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::kThreads), Cfg::kLdsBytes, st, A, M, Kdim, Ndim, B0,
+                       B1, C, hdr, table, patch);
+}
+
+int launch_grouped_ffn(const void *xp, int dtype, int64_t M, int64_t H, int64_t F, int E_local,
+                       const int32_t *seg_offsets, const void *W_gate, const void *W_up,
+                       const void *W_down, void *y, void *ws, hipStream_t st)
+{
+    if (dtype == MOE_F32) {
+        float *a = static_cast<float *>(ws);
+        hipLaunchKernelGGL(ffn_f32_gate_up, dim3((unsigned)ceil_div(M * F, 256)), dim3(256), 0, st,
+                           static_cast<const float *>(xp), M, (int)H, (int)F, E_local, seg_offsets,
+                           static_cast<const float *>(W_gate), static_cast<const float *>(W_up), a);
+        hipLaunchKernelGGL(ffn_f32_down, dim3((unsigned)ceil_div(M * H, 256)), dim3(256), 0, st, a, M,
+                           (int)H, (int)F, E_local, seg_offsets, static_cast<const float *>(W_down),
+                           static_cast<float *>(y));
+        return check_launch("moe_grouped_ffn(f32)");
+    }
+    if (H % 64 != 0 || F % 64 != 0)
+        return fail(MOE_ERR_UNSUPPORTED, "bf16 moe_grouped_ffn needs H and F to be multiples of 64 (got H=%lld, F=%lld)",
+                    (long long)H, (long long)F);
+    const FfnPlan p = make_plan(M, H, F, E_local);
+    unsigned char *w = static_cast<unsigned char *>(ws);
+    uint16_t *a = reinterpret_cast<uint16_t *>(w + p.off_a);
+    TileTableHeader *hdr1 = reinterpret_cast<TileTableHeader *>(w + p.off_hdr1);
+    TileEntry *tab1 = reinterpret_cast<TileEntry *>(w + p.off_tab1);
+    TileTableHeader *hdr2 = reinterpret_cast<TileTableHeader *>(w + p.off_hdr2);
+    TileEntry *tab2 = reinterpret_cast<TileEntry *>(w + p.off_tab2);
+    const int max1 = p.max_m_tiles * p.n_tiles1, max2 = p.max_m_tiles * p.n_tiles2;
+    hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(max1, kSchedThreads)),
+                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles1, max1,
+                       hdr1, tab1);
+    hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(max2, kSchedThreads)),
+                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles2, max2,
+                       hdr2, tab2);
+    const uint16_t *xpb = static_cast<const uint16_t *>(xp);
+    const uint16_t *wg = static_cast<const uint16_t *>(W_gate), *wu = static_cast<const uint16_t *>(W_up),
+                   *wd = static_cast<const uint16_t *>(W_down);
+    uint16_t *yb = static_cast<uint16_t *>(y);
+    const int patch = 32;
+    if (p.big) {
+        launch_gemm<256, 256, 64, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, a, hdr1, tab1, max1, patch, st);
+        launch_gemm<256, 256, 64, 2, 2, false>(a, M, (int)F, (int)H, wd, nullptr, yb, hdr2, tab2, max2, patch, st);
+    } else {
+        launch_gemm<128, 128, 64, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, a, hdr1, tab1, max1, patch, st);
+        launch_gemm<128, 128, 64, 2, 2, false>(a, M, (int)F, (int)H, wd, nullptr, yb, hdr2, tab2, max2, patch, st);
+    }
+    return check_launch("moe_grouped_ffn");
+}
+
+}  // namespace moe

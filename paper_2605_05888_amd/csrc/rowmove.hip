@@ -1,0 +1,123 @@
+// Row moves of the dispatch and combine steps (Section II-A, steps 2, 4, 5).
+// Both are pure HBM traffic: 16-byte vector accesses, one wavefront per token,
+// whole rows contiguous so every access is fully coalesced.
+//
+//   permute : x[n,:] is read once and written to its K slots.
+//             algorithmic bytes = N*H*b (read) + N*K*H*b (write) + 4*N*K (slots)
+//   combine : K rows are gathered per token, scaled, summed in fp32 (k ascending)
+//             and rounded once.  bytes = N*K*H*b (read) + N*H*b (write) + 8*N*K
+#include "common.h"
+
+namespace moe {
+
+constexpr int kTokensPerBlock = 4; // one wavefront each
+
+__global__ __launch_bounds__(kWave *kTokensPerBlock) void permute_rows(
+    const u32x4 *__restrict__ x, int chunks, int64_t N, int K,
+    const int32_t *__restrict__ slot_of_row, u32x4 *__restrict__ xp)
+{
+    const int lane = threadIdx.x % kWave;
+    const int64_t n = (int64_t)blockIdx.x * kTokensPerBlock + threadIdx.x / kWave;
+    if (n >= N)
+        return;
+    // lane k keeps slot k of this token
+    int32_t my_slot = (lane < K) ? slot_of_row[n * K + lane] : 0;
+    const u32x4 *src = x + n * chunks;
+    int c = lane;
+    for (; c + 3 * kWave < chunks; c += 4 * kWave) {
+        u32x4 v0 = __builtin_nontemporal_load(src + c);
+        u32x4 v1 = __builtin_nontemporal_load(src + c + kWave);
+        u32x4 v2 = __builtin_nontemporal_load(src + c + 2 * kWave);
+        u32x4 v3 = __builtin_nontemporal_load(src + c + 3 * kWave);
+        for (int k = 0; k < K; ++k) {
+            u32x4 *dst = xp + (int64_t)__shfl(my_slot, k) * chunks + c;
+            dst[0] = v0;
+            dst[kWave] = v1;
+            dst[2 * kWave] = v2;
+            dst[3 * kWave] = v3;
+        }
+    }
+    for (; c < chunks; c += kWave) {
+        u32x4 v = __builtin_nontemporal_load(src + c);
+        for (int k = 0; k < K; ++k)
+            xp[(int64_t)__shfl(my_slot, k) * chunks + c] = v;
+    }
+}
+
+template <bool kBf16>
+__global__ __launch_bounds__(kWave *kTokensPerBlock) void combine_rows(
+    const u32x4 *__restrict__ y, int chunks, int64_t N, int K,
+    const int32_t *__restrict__ slot_of_row, const float *__restrict__ topk_w,
+    u32x4 *__restrict__ out)
+{
+    const int lane = threadIdx.x % kWave;
+    const int64_t n = (int64_t)blockIdx.x * kTokensPerBlock + threadIdx.x / kWave;
+    if (n >= N)
+        return;
+    int32_t my_slot = (lane < K) ? slot_of_row[n * K + lane] : 0;
+    float my_w = (lane < K) ? topk_w[n * K + lane] : 0.0f;
+    for (int c = lane; c < chunks; c += kWave) {
+        float acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            acc[i] = 0.0f;
+        for (int k = 0; k < K; ++k) {
+            const float w = __shfl(my_w, k);
+            const u32x4 v = y[(int64_t)__shfl(my_slot, k) * chunks + c];
+            if (kBf16) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    acc[2 * i] = fmaf(w, bf16_bits_to_f32(v[i] & 0xFFFFu), acc[2 * i]);
+                    acc[2 * i + 1] = fmaf(w, __uint_as_float(v[i] & 0xFFFF0000u), acc[2 * i + 1]);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    acc[i] = fmaf(w, __uint_as_float(v[i]), acc[i]);
+            }
+        }
+        u32x4 o;
+        if (kBf16) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                o[i] = pack_bf16x2(acc[2 * i], acc[2 * i + 1]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                o[i] = __float_as_uint(acc[i]);
+        }
+        out[n * chunks + c] = o;
+    }
+}
+
+int launch_permute(const void *x, int64_t row_bytes, int64_t N, int K, const int32_t *slot_of_row,
+                   void *xp, hipStream_t st)
+{
+    if (K > kWave)
+        return fail(MOE_ERR_UNSUPPORTED, "moe_permute supports K <= %d (got %d)", kWave, K);
+    const int chunks = (int)(row_bytes / 16);
+    const unsigned blocks = (unsigned)ceil_div(N, kTokensPerBlock);
+    hipLaunchKernelGGL(permute_rows, dim3(blocks), dim3(kWave * kTokensPerBlock), 0, st,
+                       static_cast<const u32x4 *>(x), chunks, N, K, slot_of_row,
+                       static_cast<u32x4 *>(xp));
+    return check_launch("moe_permute");
+}
+
+int launch_combine(const void *y, int dtype, int64_t N, int64_t H, int K,
+                   const int32_t *slot_of_row, const float *topk_w, void *out, hipStream_t st)
+{
+    const unsigned blocks = (unsigned)ceil_div(N, kTokensPerBlock);
+    const dim3 block(kWave * kTokensPerBlock);
+    if (dtype == MOE_BF16) {
+        hipLaunchKernelGGL(combine_rows<true>, dim3(blocks), block, 0, st,
+                           static_cast<const u32x4 *>(y), (int)(H * 2 / 16), N, K, slot_of_row,
+                           topk_w, static_cast<u32x4 *>(out));
+    } else {
+        hipLaunchKernelGGL(combine_rows<false>, dim3(blocks), block, 0, st,
+                           static_cast<const u32x4 *>(y), (int)(H * 4 / 16), N, K, slot_of_row,
+                           topk_w, static_cast<u32x4 *>(out));
+    }
+    return check_launch("moe_combine");
+}
+
+}  // namespace moe

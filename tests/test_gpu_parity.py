@@ -1,0 +1,271 @@
+"""GPU parity: every step of the HIP path, through the C ABI, against the CPU oracle
+on the same seeded inputs.  Integers bit-exact; floats within the stated bar.
+Sizes are small enough for the oracle to compute everything, yet span several
+tiles, ragged tails and the degenerate cases of each step."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import moe_inputs as mi  # noqa: E402
+import oracle  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import gpu_layer
+    import paper_2605_05888_amd as hub
+    hub.load_library(build_if_missing=False)   # the built HIP library must be there
+    return gpu_layer
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# small stand-ins with the routing structure (E, K, G, skew, score mode, dtype) of the five workloads
+SMALL = {
+    "tiny": mi.CONFIGS["tiny"],
+    "mixtral": mi.small_variant(mi.CONFIGS["mixtral"], N=1000, H=256, F=320),
+    "gptoss": mi.small_variant(mi.CONFIGS["gptoss"], N=777, H=192, F=192),
+    "dsv3": mi.small_variant(mi.CONFIGS["dsv3"], N=515, H=128, F=64),
+    "dsv3_ep": mi.small_variant(mi.CONFIGS["dsv3_ep"], N=300, H=128, F=128),
+}
+
+
+def test_device_fill_equals_host_generator(G):
+    import moe_inputs.device as mid
+    cfg = SMALL["gptoss"]
+    for s in (mi.STREAM_X, mi.STREAM_W_ROUTER, mi.STREAM_W_GATE, mi.STREAM_W_DOWN):
+        assert np.array_equal(G.host(mid.device_tensor(cfg, s)), mi.host_tensor(cfg, s)), s
+    big = mi.CONFIGS["dsv3"]                       # far into a large tensor (flat index > 2^32)
+    d = mid.device_tensor(big, mi.STREAM_W_UP, 200, 1)
+    h = mi.host_tensor(big, mi.STREAM_W_UP, 200, 1)
+    assert np.array_equal(G.host(d), h)
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_route_parity(G, name):
+    import moe_inputs.device as mid
+    cfg = SMALL[name]
+    _say("route", cfg)
+    x, Wr = mi.host_tensor(cfg, mi.STREAM_X), mi.host_tensor(cfg, mi.STREAM_W_ROUTER)
+    bias = mi.router_bias(cfg)
+    o_idx, o_w, o_lg = oracle.route(x, Wr, bias, cfg.K, cfg.score_mode)
+    dbias = None if bias is None else mid.to_device(bias)
+    for want_logits in (True, False):
+        idx, w, lg = G.gpu_route(mid.to_device(x), mid.to_device(Wr), dbias, cfg.K, cfg.score_mode, want_logits)
+        if want_logits:
+            assert np.array_equal(G.host(lg).view(np.uint32), o_lg.view(np.uint32))   # same bits
+        assert np.array_equal(G.host(idx), o_idx)
+        assert np.max(np.abs(G.host(w).astype(np.float64) - o_w)) <= 2e-6
+
+
+@pytest.mark.parametrize("N,H,E,K,dtype", [(1, 8, 1, 1, mi.BF16), (9, 200, 5, 5, mi.BF16), (70, 72, 12, 3, mi.F32),
+                                           (33, 1000, 70, 6, mi.BF16), (5, 64, 1024, 32, mi.F32)])
+def test_route_ragged_shapes_and_ties(G, N, H, E, K, dtype):
+    import moe_inputs.device as mid
+    import dataclasses
+    cfg = dataclasses.replace(mi.CONFIGS["tiny"], N=N, H=H, E=E, K=K, dtype=dtype, seed=11)
+    _say("route ragged", cfg)
+    x, Wr = mi.host_tensor(cfg, mi.STREAM_X), mi.host_tensor(cfg, mi.STREAM_W_ROUTER)
+    Wr = np.round(Wr * 4 * np.sqrt(H)) / 4                    # coarse weights
+    if E > 2:
+        Wr[:, 2] = Wr[:, 0]                                   # experts 0 and 2 always tie
+    bias = np.zeros(E, np.float32)
+    o_idx, o_w, o_lg = oracle.route(x, Wr, bias, K, oracle.SIGMOID_TOPK)
+    idx, w, lg = G.gpu_route(mid.to_device(x), mid.to_device(Wr.astype(np.float32)), mid.to_device(bias), K,
+                             oracle.SIGMOID_TOPK)
+    assert np.array_equal(G.host(lg).view(np.uint32), o_lg.view(np.uint32))
+    assert np.array_equal(G.host(idx), o_idx)
+    assert np.max(np.abs(G.host(w).astype(np.float64) - o_w)) <= 2e-6
+
+
+def _random_idx(rng, N, E, K, skew):
+    p = None
+    if skew:
+        p = 1.0 / np.arange(1, E + 1) ** skew
+        p /= p.sum()
+    return np.stack([rng.choice(E, size=K, replace=False, p=p) for _ in range(N)]).astype(np.int32)
+
+
+LAYOUT_CASES = [(0, 8, 2, 2, 0), (1, 1, 1, 1, 0), (3, 4, 2, 4, 0), (64, 8, 1, 1, 0), (513, 8, 2, 1, 0),
+                (1000, 128, 4, 1, 1.0), (4097, 256, 8, 32, 1.2), (2000, 256, 8, 256, 0), (700, 6, 6, 3, 0),
+                (300, 1000, 16, 8, 0.5), (5000, 2, 1, 2, 2.0)]
+
+
+@pytest.mark.parametrize("N,E,K,Gd,skew", LAYOUT_CASES)
+def test_layout_parity(G, N, E, K, Gd, skew):
+    import moe_inputs.device as mid
+    _say("layout", N, E, K, Gd, skew)
+    rng = np.random.default_rng(N + E)
+    idx = _random_idx(rng, N, E, K, skew) if N else np.zeros((0, K), np.int32)
+    want = oracle.layout(idx, E, Gd)
+    got = G.gpu_layout(mid.to_device(idx).reshape(N, K), E, Gd)
+    for k in want:
+        assert np.array_equal(G.host(got[k]), want[k]), k
+    again = G.gpu_layout(mid.to_device(idx).reshape(N, K), E, Gd)    # deterministic
+    for k in want:
+        assert np.array_equal(G.host(again[k]), want[k]), k
+
+
+def test_layout_all_rows_to_one_expert(G):
+    import moe_inputs.device as mid
+    idx = np.full((3000, 1), 37, np.int32)
+    want = oracle.layout(idx, 64, 8)
+    got = G.gpu_layout(mid.to_device(idx), 64, 8)
+    for k in want:
+        assert np.array_equal(G.host(got[k]), want[k]), k
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_permute_and_combine_parity(G, name):
+    import moe_inputs.device as mid
+    cfg = SMALL[name]
+    _say("permute/combine", cfg)
+    x = mi.host_tensor(cfg, mi.STREAM_X)
+    rng = np.random.default_rng(cfg.seed)
+    idx = _random_idx(rng, cfg.N, cfg.E, cfg.K, cfg.zipf_s)
+    lay = oracle.layout(idx, cfg.E, cfg.G)
+    dlay = {k: mid.to_device(v) for k, v in lay.items()}
+    xp = G.gpu_permute(mid.to_device(x), cfg.K, dlay)
+    want_xp = oracle.permute(x, cfg.K, lay["slot_of_row"])
+    assert np.array_equal(G.host(xp), want_xp)                       # bitwise
+    w = rng.random((cfg.N, cfg.K))
+    w /= w.sum(axis=1, keepdims=True)
+    w32 = w.astype(np.float32)
+    # combine over identity experts (y = xp) and over unrelated y
+    for y in (want_xp, mi.host_tensor(mi.small_variant(cfg, N=cfg.R, H=cfg.H, F=cfg.F), mi.STREAM_X)):
+        out = G.gpu_combine(mid.to_device(y), cfg.K, dlay["slot_of_row"], mid.to_device(w32))
+        want = oracle.combine(y, cfg.K, lay["slot_of_row"], w32.astype(np.float64))
+        tol = (2e-2, 4e-3) if cfg.dtype == mi.BF16 else (1e-5, 1e-6)
+        G.check_close(G.host(out), want, *tol, what="combine")
+
+
+def _segments(rng, M, E, empty=()):
+    cuts = np.sort(rng.integers(0, M + 1, size=E - 1))
+    seg = np.concatenate([[0], cuts, [M]]).astype(np.int32)
+    for e in empty:
+        seg[e + 1] = seg[e]
+    seg = np.maximum.accumulate(seg)
+    seg[-1] = M
+    return seg
+
+
+FFN_CASES = [  # M, H, F, E_local, dtype, empty experts
+    (300, 128, 192, 5, mi.BF16, (1,)),        # small-tile plan, ragged rows and columns
+    (1500, 256, 320, 3, mi.BF16, ()),         # big-tile plan, several row tiles, F not a tile multiple
+    (900, 64, 64, 1, mi.BF16, ()),            # one expert
+    (130, 192, 448, 40, mi.BF16, (0, 7, 39)), # many tiny experts, some empty
+    (512, 128, 256, 8, mi.F32, ()),           # fp32 path
+    (77, 36, 20, 3, mi.F32, (1,)),            # fp32, odd sizes
+]
+
+
+@pytest.mark.parametrize("M,H,F,E,dtype,empty", FFN_CASES)
+def test_grouped_ffn_parity(G, M, H, F, E, dtype, empty):
+    import moe_inputs.device as mid
+    import dataclasses
+    cfg = dataclasses.replace(mi.CONFIGS["tiny"], N=M, H=H, F=F, E=E, K=1, dtype=dtype, seed=21)
+    _say("ffn", cfg)
+    rng = np.random.default_rng(M)
+    seg = _segments(rng, M, E, empty)
+    xp = mi.host_tensor(cfg, mi.STREAM_X)
+    Wg, Wu, Wd = (mi.host_tensor(cfg, s) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    want = oracle.ffn_rows(xp, seg, Wg, Wu, Wd)
+    y = G.gpu_ffn(mid.to_device(xp), mid.to_device(seg), mid.to_device(Wg), mid.to_device(Wu), mid.to_device(Wd))
+    ma, rl = G.check_close(G.host(y), want, *G.tolerances(cfg), what="ffn")
+    _say("   max-abs %.3e rel-L2 %.3e" % (ma, rl))
+
+
+def test_grouped_ffn_leaves_rows_outside_segments_untouched(G):
+    import moe_inputs.device as mid
+    import dataclasses
+    import torch
+    cfg = dataclasses.replace(mi.CONFIGS["mixtral"], N=400, H=128, F=128, E=2, K=1, seed=5)
+    xp = mi.host_tensor(cfg, mi.STREAM_X)
+    Wg, Wu, Wd = (mi.host_tensor(cfg, s) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    seg = np.array([10, 150, 390], np.int32)              # rows 0..9 and 390..399 belong to nobody
+    y = G.gpu_ffn(mid.to_device(xp), mid.to_device(seg), mid.to_device(Wg), mid.to_device(Wu), mid.to_device(Wd))
+    yh = G.host(y)
+    assert not yh[:10].any() and not yh[390:].any()        # still the zeros the buffer started with
+    want = oracle.ffn_rows(xp, seg, Wg, Wu, Wd, rows=np.arange(10, 390))
+    G.check_close(yh[10:390], want, 2e-2, 1e-2, what="ffn inner rows")
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_whole_layer_parity(G, name):
+    """route -> layout -> permute -> grouped FFN -> combine, each GPU step fed by the GPU's own outputs."""
+    import moe_inputs.device as mid
+    cfg = SMALL[name]
+    _say("layer", cfg)
+    x, Wr = mi.host_tensor(cfg, mi.STREAM_X), mi.host_tensor(cfg, mi.STREAM_W_ROUTER)
+    Wg, Wu, Wd = (mi.host_tensor(cfg, s) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    bias = mi.router_bias(cfg)
+    # oracle chain
+    o_idx, o_w, _ = oracle.route(x, Wr, bias, cfg.K, cfg.score_mode)
+    o_lay = oracle.layout(o_idx, cfg.E, cfg.G)
+    o_xp = oracle.permute(x, cfg.K, o_lay["slot_of_row"])
+    o_y = oracle.ffn_rows(o_xp, o_lay["expert_offsets"], Wg, Wu, Wd)
+    o_out = oracle.combine(o_y, cfg.K, o_lay["slot_of_row"], o_w)
+    # GPU chain
+    dx = mid.to_device(x)
+    idx, w, _ = G.gpu_route(dx, mid.to_device(Wr), None if bias is None else mid.to_device(bias), cfg.K,
+                            cfg.score_mode, want_logits=False)
+    lay = G.gpu_layout(idx, cfg.E, cfg.G)
+    xp = G.gpu_permute(dx, cfg.K, lay)
+    y = G.gpu_ffn(xp, lay["expert_offsets"], mid.to_device(Wg), mid.to_device(Wu), mid.to_device(Wd))
+    out = G.gpu_combine(y, cfg.K, lay["slot_of_row"], w)
+    assert np.array_equal(G.host(idx), o_idx)
+    for k in o_lay:
+        assert np.array_equal(G.host(lay[k]), o_lay[k]), k
+    assert np.array_equal(G.host(xp), o_xp)
+    tol = G.tolerances(cfg)
+    G.check_close(G.host(y), o_y, *tol, what="y")
+    ma, rl = G.check_close(G.host(out), o_out, *tol, what="out")
+    _say("   out max-abs %.3e rel-L2 %.3e" % (ma, rl))
+
+
+def test_expert_parallel_rank_share(G):
+    """One destination's 8 local experts: FFN over rows [dest_offsets[g], dest_offsets[g+1]) only."""
+    import moe_inputs.device as mid
+    cfg = SMALL["dsv3_ep"]
+    Eg = cfg.E // cfg.G
+    g = 3
+    x, Wr = mi.host_tensor(cfg, mi.STREAM_X), mi.host_tensor(cfg, mi.STREAM_W_ROUTER)
+    o_idx, _, _ = oracle.route(x, Wr, mi.router_bias(cfg), cfg.K, cfg.score_mode)
+    o_lay = oracle.layout(o_idx, cfg.E, cfg.G)
+    o_xp = oracle.permute(x, cfg.K, o_lay["slot_of_row"])
+    Wg, Wu, Wd = (mi.host_tensor(cfg, s, g * Eg, Eg) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    seg = o_lay["expert_offsets"][g * Eg:(g + 1) * Eg + 1]
+    lo, hi = int(o_lay["dest_offsets"][g]), int(o_lay["dest_offsets"][g + 1])
+    assert lo == seg[0] and hi == seg[-1]
+    want = oracle.ffn_rows(o_xp, seg, Wg, Wu, Wd, rows=np.arange(lo, hi))
+    dlay = G.gpu_layout(mid.to_device(o_idx), cfg.E, cfg.G)
+    y = G.gpu_ffn(mid.to_device(o_xp), dlay["expert_offsets"][g * Eg:(g + 1) * Eg + 1].contiguous(),
+                  mid.to_device(Wg), mid.to_device(Wu), mid.to_device(Wd))
+    yh = G.host(y)
+    G.check_close(yh[lo:hi], want, 2e-2, 1e-2, what="local experts")
+    assert not yh[:lo].any() and not yh[hi:].any()
+
+
+def test_error_returns_launch_nothing(G):
+    import torch
+    import paper_2605_05888_amd as hub
+    x = torch.zeros((4, 64), dtype=torch.bfloat16, device="cuda:0")
+    xp = torch.full((8, 64), 3.0, dtype=torch.bfloat16, device="cuda:0")
+    s = torch.zeros(8, dtype=torch.int32, device="cuda:0")
+    lib = hub.load_library()
+    rc = lib.moe_permute(x.data_ptr(), 7, 4, 64, 2, s.data_ptr(), s.data_ptr(), xp.data_ptr(), None)
+    assert rc == -2 and "dtype" in hub.last_error()
+    rc = lib.moe_permute(x.data_ptr(), hub.BF16, 4, 60, 2, s.data_ptr(), s.data_ptr(), xp.data_ptr(), None)
+    assert rc == -1
+    torch.cuda.synchronize()
+    assert bool((xp == 3.0).all())                              # output untouched
+    with pytest.raises(hub.MoEHubError):
+        G.hub.moe_grouped_ffn(xp, s[:2].contiguous(), torch.zeros((1, 64, 64), dtype=torch.bfloat16, device="cuda:0"),
+                              torch.zeros((1, 64, 64), dtype=torch.bfloat16, device="cuda:0"),
+                              torch.zeros((1, 64, 64), dtype=torch.bfloat16, device="cuda:0"),
+                              torch.zeros_like(xp), None)       # missing workspace
