@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""MoE-layer hot-path benchmark on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic tokens:
+    moe_route -> moe_dispatch_layout -> moe_permute -> moe_ffn_schedule ->
+    moe_ffn_gate_up -> moe_ffn_down -> moe_combine
+all enqueued on one stream through the C ABI, inputs resident in HBM.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mixtral]
+
+Prints ONE JSON line: layer tokens/s, the roofline of the dominant kernel
+(the gate/up grouped GEMM, timed live with HIP events), the HBM rate of the
+permute and combine row moves, and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+WORKLOAD_TEXT = {
+    "tiny": "Tiny MoE layer (fp32)",
+    "mixtral": "Mixtral-8x7B-shaped layer",
+    "gptoss": "gpt-oss-shaped layer, Zipf(1.0) expert popularity",
+    "dsv3": "DeepSeek-V3-shaped routed layer",
+    "dsv3_ep": "one expert-parallel rank's share of a DeepSeek-V3-shaped layer (32 destinations, 8 local experts)",
+}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="mixtral", choices=list(WORKLOAD_TEXT))
+    ap.add_argument("--nbuf", type=int, default=0, help="activation buffer sets rotated per step (0 = auto)")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample (0 = skip)")
+    return ap.parse_args()
+
+
+class Layer:
+    """Device buffers of one workload and the step that walks the C ABI."""
+
+    def __init__(self, cfg, nbuf):
+        import torch
+        import moe_inputs as mi
+        import moe_inputs.device as mid
+        import paper_2605_05888_amd as hub
+        self.cfg, self.hub, self.torch = cfg, hub, torch
+        dev = "cuda:0"
+        dt = torch.bfloat16 if cfg.dtype == mi.BF16 else torch.float32
+        self.code = hub.BF16 if cfg.dtype == mi.BF16 else hub.F32
+        N, H, E, K, F, G = cfg.N, cfg.H, cfg.E, cfg.K, cfg.F, cfg.G
+        R = N * K
+        self.R = R
+        self.ep = G > 1
+        self.E_local = E // G
+        # weights: router for all experts; expert weights for the experts this GPU computes
+        self.W_r = mid.device_tensor(cfg, mi.STREAM_W_ROUTER)
+        bias = mi.router_bias(cfg)
+        self.bias = None if bias is None else mid.to_device(bias)
+        self.W_gate = mid.device_tensor(cfg, mi.STREAM_W_GATE, 0, self.E_local)
+        self.W_up = mid.device_tensor(cfg, mi.STREAM_W_UP, 0, self.E_local)
+        self.W_down = mid.device_tensor(cfg, mi.STREAM_W_DOWN, 0, self.E_local)
+        x0 = mid.device_tensor(cfg, mi.STREAM_X)
+        self.sets = []
+        i32 = dict(dtype=torch.int32, device=dev)
+        ffn_ws = hub.workspace_bytes(hub.OP_GROUPED_FFN, N=R, H=H, E=self.E_local, F=F, dtype=self.code)
+        for i in range(nbuf):
+            s = dict(
+                x=x0 if i == 0 else x0.clone(),
+                idx=torch.empty((N, K), **i32), w=torch.empty((N, K), dtype=torch.float32, device=dev),
+                cnt=torch.empty(E, **i32), off=torch.empty(E + 1, **i32),
+                dcnt=torch.empty(G, **i32), doff=torch.empty(G + 1, **i32),
+                slot=torch.empty(R, **i32), row=torch.empty(R, **i32),
+                xp=torch.empty((R, H), dtype=dt, device=dev), y=torch.empty((R, H), dtype=dt, device=dev),
+                out=torch.empty((N, H), dtype=dt, device=dev),
+                ffn_ws=torch.empty(ffn_ws, dtype=torch.uint8, device=dev))
+            self.sets.append(s)
+        self.route_ws = torch.empty(hub.workspace_bytes(hub.OP_ROUTE, N=N, E=E), dtype=torch.uint8, device=dev)
+        self.layout_ws = torch.empty(max(16, hub.workspace_bytes(hub.OP_DISPATCH_LAYOUT, N=N, E=E, K=K, G=G)),
+                                     dtype=torch.uint8, device=dev)
+        if self.ep:
+            # what the peers would send: R rows for the local experts, split by their popularity
+            self.recv = mid.fill_normal(torch.empty((R, H), dtype=dt, device=dev), cfg.seed, mi.STREAM_RECV_X, 0, 1.0)
+            import numpy as np
+            c = mi.recv_segment_counts(cfg, R, 0)
+            seg = np.concatenate([[0], np.cumsum(c)]).astype(np.int32)
+            self.recv_seg = mid.to_device(seg)
+        self.names = ["route", "layout", "permute", "ffn_schedule", "ffn_gate_up", "ffn_down", "combine"]
+
+    def step(self, i, events=None):
+        hub, cfg = self.hub, self.cfg
+        s = self.sets[i % len(self.sets)]
+        rec = (lambda j: events[j].record()) if events is not None else (lambda j: None)
+        rec(0)
+        hub.moe_route(s["x"], self.W_r, self.bias, cfg.K, cfg.score_mode, s["idx"], s["w"], None, self.route_ws)
+        rec(1)
+        hub.moe_dispatch_layout(s["idx"], cfg.E, cfg.G, s["cnt"], s["off"], s["dcnt"], s["doff"], s["slot"],
+                                s["row"], self.layout_ws)
+        rec(2)
+        hub.moe_permute(s["x"], cfg.K, s["slot"], s["row"], s["xp"])
+        rec(3)
+        if self.ep:
+            ffn_in, seg = self.recv, self.recv_seg
+        else:
+            ffn_in, seg = s["xp"], s["off"]
+        hub.moe_ffn_schedule(self.code, self.R, cfg.H, cfg.F, seg, s["ffn_ws"])
+        rec(4)
+        hub.moe_ffn_gate_up(ffn_in, seg, self.W_gate, self.W_up, s["ffn_ws"])
+        rec(5)
+        hub.moe_ffn_down(seg, self.W_down, s["y"], s["ffn_ws"])
+        rec(6)
+        hub.moe_combine(s["y"], cfg.K, s["slot"], s["w"], s["out"])
+        rec(7)
+
+
+def cpu_baseline(cfg, layer, target_seconds):
+    """The oracle, as it stands, on a bounded sample of the same workload: a mini-batch of S
+    tokens through the whole layer (all experts, full H and F).  tokens/s = S / elapsed."""
+    import numpy as np
+    import moe_inputs as mi
+    import moe_inputs.device as mid
+    import oracle
+    Wr = mid.to_host(layer.W_r)
+    bias = None if layer.bias is None else mid.to_host(layer.bias)
+    E_run = layer.E_local if layer.ep else cfg.E
+    Wg, Wu, Wd = mid.to_host(layer.W_gate), mid.to_host(layer.W_up), mid.to_host(layer.W_down)
+    x_all = mid.to_host(layer.sets[0]["x"])
+
+    def run(S):
+        x = x_all[:S]
+        t0 = time.perf_counter()
+        idx, w, _ = oracle.route(x, Wr, bias, cfg.K, cfg.score_mode)
+        lay = oracle.layout(idx, cfg.E, cfg.G)
+        xp = oracle.permute(x, cfg.K, lay["slot_of_row"])
+        if layer.ep:   # the local experts see S*K received rows, split as in the GPU run
+            c = mi.recv_segment_counts(cfg, S * cfg.K, 0)
+            seg = np.concatenate([[0], np.cumsum(c)]).astype(np.int32)
+        else:
+            seg = lay["expert_offsets"]
+        y = oracle.ffn_rows(xp, seg, Wg[:E_run], Wu[:E_run], Wd[:E_run])
+        oracle.combine(y, cfg.K, lay["slot_of_row"], w)
+        return time.perf_counter() - t0
+
+    S = min(cfg.N, 16)
+    t = run(S)
+    S2 = int(max(S, min(cfg.N, S * target_seconds / max(t, 1e-3))))
+    if S2 > S:
+        S, t = S2, run(S2)
+    return {"value": S / t, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{S} of {cfg.N} tokens through the whole layer (route, layout, permute, fp64 SwiGLU FFN "
+                      f"over all {E_run} experts at full H and F, combine); {t:.1f} s of CPU time"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; there is no multi-GPU path to time "
+              f"(--gpus {args.gpus} refused).", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    import moe_inputs as mi
+    import paper_2605_05888_amd as hub
+    hub.load_library(build_if_missing=False)     # fail loudly if the HIP library is not built
+    cfg = mi.CONFIGS[args.workload]
+    N, H, E, K, F, G = cfg.N, cfg.H, cfg.E, cfg.K, cfg.F, cfg.G
+    R, b = N * K, cfg.elt_bytes
+    act_bytes = (2 * N * H + 2 * R * H + R * F) * b
+    nbuf = args.nbuf or (4 if act_bytes < (1 << 30) else 1)   # rotate small working sets out of the 256 MB cache
+    layer = Layer(cfg, nbuf)
+    torch.cuda.synchronize()
+
+    for i in range(args.warmup):
+        layer.step(i)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        layer.step(i, ev[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    us = {n: sum(e[j].elapsed_time(e[j + 1]) for e in ev) * 1e3 / args.steps for j, n in enumerate(layer.names)}
+
+    flops_gu = 4.0 * R * H * F                  # gate and up projections: 2 * (2*R*H*F)
+    flops_dn = 2.0 * R * H * F
+    t_gu, t_dn = us["ffn_gate_up"] * 1e-6, us["ffn_down"] * 1e-6
+    ach = flops_gu / t_gu / 1e12
+    move_bytes = N * H * b + R * H * b          # permute: read x once, write xp; combine: the mirror image
+    gbs_perm = (move_bytes + 4 * R) / (us["permute"] * 1e-6) / 1e9
+    gbs_comb = (move_bytes + 8 * R) / (us["combine"] * 1e-6) / 1e9
+    result = {
+        "metric": "moe_layer_tokens_per_s", "value": N / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == mi.BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {WORKLOAD_TEXT[args.workload]}", "N": N, "H": H, "E": E, "K": K,
+                   "F": F, "G": G, "routed_rows": R, "activation_buffer_sets": nbuf},
+        "roofline": {"kernel": "grouped_gemm_bf16 (gate/up projection with fused SwiGLU)", "bound": "mfma",
+                     "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                     "flops_per_launch": flops_gu, "avg_launch_us": us["ffn_gate_up"], "traffic": None},
+        "ffn": {"tflops_gate_up": ach, "tflops_down": flops_dn / t_dn / 1e12,
+                "tflops_both": (flops_gu + flops_dn) / (t_gu + t_dn) / 1e12,
+                "mfma_frac_both": (flops_gu + flops_dn) / (t_gu + t_dn) / 1e12 / PEAK_BF16_TFLOPS},
+        "dispatch_combine": {"permute_GBs": gbs_perm, "combine_GBs": gbs_comb, "peak_GBs": PEAK_HBM_GBS,
+                             "permute_frac": gbs_perm / PEAK_HBM_GBS, "combine_frac": gbs_comb / PEAK_HBM_GBS},
+        "step_breakdown_us": us,
+    }
+    if args.cpu_seconds > 0:
+        result["cpu_baseline"] = cpu_baseline(cfg, layer, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -141,6 +141,27 @@ int moe_grouped_ffn(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
                     void *y, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The same computation in its three parts, for callers that want to time or
+ * overlap the two GEMMs of Section II-A step 3 separately ("GEMM1" = gate and up
+ * projection with the activation fused, "GEMM2" = down projection).  Arguments
+ * as in moe_grouped_ffn; all three share one workspace of
+ * moe_workspace_bytes(MOE_OP_GROUPED_FFN, ...) bytes, and
+ *   moe_ffn_schedule -> moe_ffn_gate_up -> moe_ffn_down   (in stream order)
+ * is exactly moe_grouped_ffn.  moe_ffn_schedule turns seg_offsets into the
+ * device-side tile tables both GEMMs read; moe_ffn_gate_up leaves the activation
+ * a[M,F] in the workspace; moe_ffn_down reads it and writes y.
+ */
+int moe_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
+                     const int32_t *seg_offsets, void *ws, size_t ws_bytes, void *stream);
+int moe_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
+                    int E_local, const int32_t *seg_offsets,
+                    const void *W_gate, const void *W_up,
+                    void *ws, size_t ws_bytes, void *stream);
+int moe_ffn_down(int dtype, int64_t M, int64_t H, int64_t F,
+                 int E_local, const int32_t *seg_offsets, const void *W_down,
+                 void *y, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Combine and scaling (Section II-A, steps 4-5): rows return to their tokens
  * and are summed with the routing weights,
  *   out[n,:] = sum_{k=0..K-1} topk_w[n,k] * y[slot_of_row[n*K+k], :]

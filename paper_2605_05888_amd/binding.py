@@ -26,6 +26,10 @@ _SIGNATURES = {
     "moe_permute": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp, _c_vp]),
     "moe_grouped_ffn": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp,
                                  _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
+    "moe_ffn_schedule": (_c_int, [_c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_sz, _c_vp]),
+    "moe_ffn_gate_up": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp,
+                                 _c_vp, _c_sz, _c_vp]),
+    "moe_ffn_down": (_c_int, [_c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
     "moe_combine": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp, _c_vp]),
 }
 
@@ -159,6 +163,33 @@ def moe_grouped_ffn(xp, seg_offsets, W_gate, W_up, W_down, y, ws):
     wp, wb = _ws_args(ws)
     _check(load_library().moe_grouped_ffn(_ptr(xp), _dtype_code(xp), M, H, F, E_local, _ptr(seg_offsets),
                                           _ptr(W_gate), _ptr(W_up), _ptr(W_down), _ptr(y), wp, wb, _stream()))
+
+
+def moe_ffn_schedule(dtype: int, M: int, H: int, F: int, seg_offsets, ws):
+    wp, wb = _ws_args(ws)
+    _check(load_library().moe_ffn_schedule(dtype, M, H, F, seg_offsets.numel() - 1, _ptr(seg_offsets), wp, wb,
+                                           _stream()))
+
+
+def moe_ffn_gate_up(xp, seg_offsets, W_gate, W_up, ws):
+    M, H = xp.shape
+    E_local, F, _ = W_gate.shape
+    assert tuple(W_up.shape) == tuple(W_gate.shape) and W_gate.shape[2] == H
+    assert xp.is_contiguous() and W_gate.is_contiguous() and W_up.is_contiguous()
+    assert seg_offsets.numel() == E_local + 1
+    wp, wb = _ws_args(ws)
+    _check(load_library().moe_ffn_gate_up(_ptr(xp), _dtype_code(xp), M, H, F, E_local, _ptr(seg_offsets),
+                                          _ptr(W_gate), _ptr(W_up), wp, wb, _stream()))
+
+
+def moe_ffn_down(seg_offsets, W_down, y, ws):
+    M, H = y.shape
+    E_local, H2, F = W_down.shape
+    assert H2 == H and y.is_contiguous() and W_down.is_contiguous() and W_down.dtype == y.dtype
+    assert seg_offsets.numel() == E_local + 1
+    wp, wb = _ws_args(ws)
+    _check(load_library().moe_ffn_down(_dtype_code(y), M, H, F, E_local, _ptr(seg_offsets), _ptr(W_down),
+                                       _ptr(y), wp, wb, _stream()))
 
 
 def moe_combine(y, K: int, slot_of_row, topk_w, out):

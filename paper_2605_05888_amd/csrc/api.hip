@@ -188,12 +188,11 @@ extern "C" int moe_permute(const void *x, int dtype, int64_t N, int64_t H, int K
                           static_cast<hipStream_t>(stream));
 }
 
-extern "C" int moe_grouped_ffn(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
-                               int E_local, const int32_t *seg_offsets, const void *W_gate,
-                               const void *W_up, const void *W_down, void *y, void *ws,
-                               size_t ws_bytes, void *stream)
+namespace moe {
+
+static int check_ffn_common(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
+                            const int32_t *seg_offsets, void *ws, size_t ws_bytes)
 {
-    clear_error();
     MOE_TRY(check_dtype(dtype));
     MOE_TRY(check_rows("H", H, dtype));
     MOE_TRY(check_rows("F", F, dtype));
@@ -201,6 +200,68 @@ extern "C" int moe_grouped_ffn(const void *xp, int dtype, int64_t M, int64_t H, 
         return fail(MOE_ERR_ARG, "M must be in [0, 2^31) (got %lld)", (long long)M);
     if (E_local < 1 || E_local > MOE_MAX_EXPERTS)
         return fail(MOE_ERR_ARG, "E_local must be in [1, %d] (got %d)", MOE_MAX_EXPERTS, E_local);
+    MOE_TRY(check_ffn_shape(dtype, H, F));
+    if (M == 0)
+        return MOE_OK;
+    if (!seg_offsets)
+        return fail(MOE_ERR_ARG, "seg_offsets must not be NULL");
+    size_t need = ffn_workspace_bytes(M, H, F, E_local, dtype);
+    if (!ws || ws_bytes < need)
+        return fail(MOE_ERR_WORKSPACE, "the grouped FFN needs %zu workspace bytes (got %zu)", need,
+                    ws ? ws_bytes : (size_t)0);
+    if (!aligned16(ws))
+        return fail(MOE_ERR_ARG, "ws must be 16-byte aligned");
+    return MOE_OK;
+}
+
+}  // namespace moe
+
+extern "C" int moe_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
+                                const int32_t *seg_offsets, void *ws, size_t ws_bytes, void *stream)
+{
+    clear_error();
+    MOE_TRY(check_ffn_common(dtype, M, H, F, E_local, seg_offsets, ws, ws_bytes));
+    if (M == 0)
+        return MOE_OK;
+    return launch_ffn_schedule(dtype, M, H, F, E_local, seg_offsets, ws, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int moe_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
+                               int E_local, const int32_t *seg_offsets, const void *W_gate,
+                               const void *W_up, void *ws, size_t ws_bytes, void *stream)
+{
+    clear_error();
+    MOE_TRY(check_ffn_common(dtype, M, H, F, E_local, seg_offsets, ws, ws_bytes));
+    if (M == 0)
+        return MOE_OK;
+    MOE_NEED(xp);
+    MOE_NEED(W_gate);
+    MOE_NEED(W_up);
+    return launch_ffn_gate_up(xp, dtype, M, H, F, E_local, seg_offsets, W_gate, W_up, ws,
+                              static_cast<hipStream_t>(stream));
+}
+
+extern "C" int moe_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
+                            const int32_t *seg_offsets, const void *W_down, void *y, void *ws,
+                            size_t ws_bytes, void *stream)
+{
+    clear_error();
+    MOE_TRY(check_ffn_common(dtype, M, H, F, E_local, seg_offsets, ws, ws_bytes));
+    if (M == 0)
+        return MOE_OK;
+    MOE_NEED(W_down);
+    MOE_NEED(y);
+    return launch_ffn_down(dtype, M, H, F, E_local, seg_offsets, W_down, y, ws,
+                           static_cast<hipStream_t>(stream));
+}
+
+extern "C" int moe_grouped_ffn(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
+                               int E_local, const int32_t *seg_offsets, const void *W_gate,
+                               const void *W_up, const void *W_down, void *y, void *ws,
+                               size_t ws_bytes, void *stream)
+{
+    clear_error();
+    MOE_TRY(check_ffn_common(dtype, M, H, F, E_local, seg_offsets, ws, ws_bytes));
     if (M == 0)
         return MOE_OK;
     MOE_NEED(xp);
@@ -208,16 +269,10 @@ extern "C" int moe_grouped_ffn(const void *xp, int dtype, int64_t M, int64_t H, 
     MOE_NEED(W_up);
     MOE_NEED(W_down);
     MOE_NEED(y);
-    if (!seg_offsets)
-        return fail(MOE_ERR_ARG, "seg_offsets must not be NULL");
-    size_t need = ffn_workspace_bytes(M, H, F, E_local, dtype);
-    if (!ws || ws_bytes < need)
-        return fail(MOE_ERR_WORKSPACE, "moe_grouped_ffn needs %zu workspace bytes (got %zu)", need,
-                    ws ? ws_bytes : (size_t)0);
-    if (!aligned16(ws))
-        return fail(MOE_ERR_ARG, "ws must be 16-byte aligned");
-    return launch_grouped_ffn(xp, dtype, M, H, F, E_local, seg_offsets, W_gate, W_up, W_down, y,
-                              ws, static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    MOE_TRY(launch_ffn_schedule(dtype, M, H, F, E_local, seg_offsets, ws, st));
+    MOE_TRY(launch_ffn_gate_up(xp, dtype, M, H, F, E_local, seg_offsets, W_gate, W_up, ws, st));
+    return launch_ffn_down(dtype, M, H, F, E_local, seg_offsets, W_down, y, ws, st);
 }
 
 extern "C" int moe_combine(const void *y, int dtype, int64_t N, int64_t H, int K,

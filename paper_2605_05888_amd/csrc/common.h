@@ -60,8 +60,14 @@ int launch_combine(const void *y, int dtype, int64_t N, int64_t H, int K,
                    const int32_t *slot_of_row, const float *topk_w, void *out, hipStream_t st);
 
 size_t ffn_workspace_bytes(int64_t M, int64_t H, int64_t F, int E_local, int dtype);
-int launch_grouped_ffn(const void *xp, int dtype, int64_t M, int64_t H, int64_t F, int E_local,
-                       const int32_t *seg_offsets, const void *W_gate, const void *W_up,
-                       const void *W_down, void *y, void *ws, hipStream_t st);
+int check_ffn_shape(int dtype, int64_t H, int64_t F);
+int launch_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
+                        const int32_t *seg_offsets, void *ws, hipStream_t st);
+int launch_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t F, int E_local,
+                       const int32_t *seg_offsets, const void *W_gate, const void *W_up, void *ws,
+                       hipStream_t st);
+int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
+                    const int32_t *seg_offsets, const void *W_down, void *y, void *ws,
+                    hipStream_t st);
 
 }  // namespace moe

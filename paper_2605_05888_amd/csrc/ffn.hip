@@ -436,50 +436,94 @@ static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const 
                        B1, C, hdr, table, patch);
 }
 
-int launch_grouped_ffn(const void *xp, int dtype, int64_t M, int64_t H, int64_t F, int E_local,
-                       const int32_t *seg_offsets, const void *W_gate, const void *W_up,
-                       const void *W_down, void *y, void *ws, hipStream_t st)
+int check_ffn_shape(int dtype, int64_t H, int64_t F)
+{
+    if (dtype == MOE_BF16 && (H % 64 != 0 || F % 64 != 0))
+        return fail(MOE_ERR_UNSUPPORTED,
+                    "bf16 moe_grouped_ffn needs H and F to be multiples of 64 (got H=%lld, F=%lld)",
+                    (long long)H, (long long)F);
+    return MOE_OK;
+}
+
+struct FfnWorkspace {
+    uint16_t *a;
+    TileTableHeader *hdr1, *hdr2;
+    TileEntry *tab1, *tab2;
+    int max1, max2;
+};
+
+static FfnWorkspace carve(const FfnPlan &p, void *ws)
+{
+    unsigned char *w = static_cast<unsigned char *>(ws);
+    FfnWorkspace k;
+    k.a = reinterpret_cast<uint16_t *>(w + p.off_a);
+    k.hdr1 = reinterpret_cast<TileTableHeader *>(w + p.off_hdr1);
+    k.tab1 = reinterpret_cast<TileEntry *>(w + p.off_tab1);
+    k.hdr2 = reinterpret_cast<TileTableHeader *>(w + p.off_hdr2);
+    k.tab2 = reinterpret_cast<TileEntry *>(w + p.off_tab2);
+    k.max1 = p.max_m_tiles * p.n_tiles1;
+    k.max2 = p.max_m_tiles * p.n_tiles2;
+    return k;
+}
+
+constexpr int kPatch = 32;
+
+int launch_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
+                        const int32_t *seg_offsets, void *ws, hipStream_t st)
+{
+    if (dtype == MOE_F32)
+        return MOE_OK; // the fp32 kernels look their expert up per row
+    const FfnPlan p = make_plan(M, H, F, E_local);
+    const FfnWorkspace k = carve(p, ws);
+    hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(k.max1, kSchedThreads)),
+                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles1, k.max1,
+                       k.hdr1, k.tab1);
+    hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(k.max2, kSchedThreads)),
+                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles2, k.max2,
+                       k.hdr2, k.tab2);
+    return check_launch("moe_ffn_schedule");
+}
+
+int launch_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t F, int E_local,
+                       const int32_t *seg_offsets, const void *W_gate, const void *W_up, void *ws,
+                       hipStream_t st)
 {
     if (dtype == MOE_F32) {
-        float *a = static_cast<float *>(ws);
         hipLaunchKernelGGL(ffn_f32_gate_up, dim3((unsigned)ceil_div(M * F, 256)), dim3(256), 0, st,
                            static_cast<const float *>(xp), M, (int)H, (int)F, E_local, seg_offsets,
-                           static_cast<const float *>(W_gate), static_cast<const float *>(W_up), a);
-        hipLaunchKernelGGL(ffn_f32_down, dim3((unsigned)ceil_div(M * H, 256)), dim3(256), 0, st, a, M,
-                           (int)H, (int)F, E_local, seg_offsets, static_cast<const float *>(W_down),
-                           static_cast<float *>(y));
-        return check_launch("moe_grouped_ffn(f32)");
+                           static_cast<const float *>(W_gate), static_cast<const float *>(W_up),
+                           static_cast<float *>(ws));
+        return check_launch("moe_ffn_gate_up(f32)");
     }
-    if (H % 64 != 0 || F % 64 != 0)
-        return fail(MOE_ERR_UNSUPPORTED, "bf16 moe_grouped_ffn needs H and F to be multiples of 64 (got H=%lld, F=%lld)",
-                    (long long)H, (long long)F);
     const FfnPlan p = make_plan(M, H, F, E_local);
-    unsigned char *w = static_cast<unsigned char *>(ws);
-    uint16_t *a = reinterpret_cast<uint16_t *>(w + p.off_a);
-    TileTableHeader *hdr1 = reinterpret_cast<TileTableHeader *>(w + p.off_hdr1);
-    TileEntry *tab1 = reinterpret_cast<TileEntry *>(w + p.off_tab1);
-    TileTableHeader *hdr2 = reinterpret_cast<TileTableHeader *>(w + p.off_hdr2);
-    TileEntry *tab2 = reinterpret_cast<TileEntry *>(w + p.off_tab2);
-    const int max1 = p.max_m_tiles * p.n_tiles1, max2 = p.max_m_tiles * p.n_tiles2;
-    hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(max1, kSchedThreads)),
-                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles1, max1,
-                       hdr1, tab1);
-    hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(max2, kSchedThreads)),
-                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles2, max2,
-                       hdr2, tab2);
+    const FfnWorkspace k = carve(p, ws);
     const uint16_t *xpb = static_cast<const uint16_t *>(xp);
-    const uint16_t *wg = static_cast<const uint16_t *>(W_gate), *wu = static_cast<const uint16_t *>(W_up),
-                   *wd = static_cast<const uint16_t *>(W_down);
-    uint16_t *yb = static_cast<uint16_t *>(y);
-    const int patch = 32;
-    if (p.big) {
-        launch_gemm<256, 256, 64, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, a, hdr1, tab1, max1, patch, st);
-        launch_gemm<256, 256, 64, 2, 2, false>(a, M, (int)F, (int)H, wd, nullptr, yb, hdr2, tab2, max2, patch, st);
-    } else {
-        launch_gemm<128, 128, 64, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, a, hdr1, tab1, max1, patch, st);
-        launch_gemm<128, 128, 64, 2, 2, false>(a, M, (int)F, (int)H, wd, nullptr, yb, hdr2, tab2, max2, patch, st);
+    const uint16_t *wg = static_cast<const uint16_t *>(W_gate), *wu = static_cast<const uint16_t *>(W_up);
+    if (p.big)
+        launch_gemm<256, 256, 64, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
+    else
+        launch_gemm<128, 128, 64, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
+    return check_launch("moe_ffn_gate_up");
+}
+
+int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
+                    const int32_t *seg_offsets, const void *W_down, void *y, void *ws, hipStream_t st)
+{
+    if (dtype == MOE_F32) {
+        hipLaunchKernelGGL(ffn_f32_down, dim3((unsigned)ceil_div(M * H, 256)), dim3(256), 0, st,
+                           static_cast<const float *>(ws), M, (int)H, (int)F, E_local, seg_offsets,
+                           static_cast<const float *>(W_down), static_cast<float *>(y));
+        return check_launch("moe_ffn_down(f32)");
     }
-    return check_launch("moe_grouped_ffn");
+    const FfnPlan p = make_plan(M, H, F, E_local);
+    const FfnWorkspace k = carve(p, ws);
+    const uint16_t *wd = static_cast<const uint16_t *>(W_down);
+    uint16_t *yb = static_cast<uint16_t *>(y);
+    if (p.big)
+        launch_gemm<256, 256, 64, 2, 2, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
+    else
+        launch_gemm<128, 128, 64, 2, 2, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
+    return check_launch("moe_ffn_down");
 }
 
 }  // namespace moe
