@@ -17,24 +17,13 @@
 // sees a compact patch of that order.  Nothing about the routing result is read
 // on the host.
 #include "common.h"
+#include "grouped_gemm.h"
 
 namespace moe {
 
 // ------------------------------------------------------------------------
 // tile table
 // ------------------------------------------------------------------------
-struct TileEntry {
-    int32_t expert; // local expert
-    int32_t m0;     // first row of the tile
-    int32_t m_end;  // end of the expert's segment (rows >= m_end are not written)
-    int32_t n_tile; // column tile
-};
-
-struct TileTableHeader {
-    int32_t num_tiles;
-    int32_t pad[3];
-};
-
 constexpr int kSchedThreads = 256;
 
 // table[L] for L in [0, num_tiles): order = expert, then column tile, then row tile.
@@ -123,193 +112,6 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
 // ------------------------------------------------------------------------
 // bf16 matrix-core grouped GEMM
 // ------------------------------------------------------------------------
-constexpr int kXcds = 8;
-
-// Workgroup id -> position in the tile order.  Ids are dealt round-robin to the
-// 8 XCDs; each XCD takes runs of kPatch consecutive tiles so its L2 sees tiles
-// that share weight and activation rows.
-__device__ __forceinline__ int tile_of_workgroup(int id, int kPatch)
-{
-    const int xcd = id % kXcds, j = id / kXcds;
-    return (j / kPatch) * (kPatch * kXcds) + xcd * kPatch + (j % kPatch);
-}
-
-__device__ __forceinline__ float silu_mul(float g, float u)
-{
-    return g / (1.0f + __expf(-g)) * u;
-}
-
-template <int BM, int BN, int BK, int WM, int WN, bool kSwiglu>
-struct GemmCfg {
-    static constexpr int kThreads = WM * WN * kWave;
-    static constexpr int kWaveM = BM / WM;     // rows per wavefront
-    static constexpr int kWaveN = BN / WN;     // LDS B rows per wavefront
-    static constexpr int kBlkM = kWaveM / 32;  // 32x32 blocks per wavefront, M
-    static constexpr int kBlkN = kWaveN / 32;
-    static constexpr int kChunksPerRow = BK / 8; // 16-byte chunks per tile row
-    static constexpr int kAChunks = BM * kChunksPerRow / kThreads; // per thread
-    static constexpr int kBChunks = BN * kChunksPerRow / kThreads;
-    static constexpr int kOutCols = kSwiglu ? BN / 2 : BN; // output columns per tile
-    static constexpr size_t kLdsBytes = 2 * (size_t)(BM + BN) * BK * 2;
-    static_assert(kChunksPerRow == 8, "swizzle assumes 128-byte tile rows");
-    static_assert(kWaveM % 32 == 0 && kWaveN % 32 == 0, "wave tile must be 32x32 blocks");
-    static_assert(!kSwiglu || kBlkN % 2 == 0, "gate and up halves");
-};
-
-// byte offset of 16-byte chunk `c` of tile row `r` (rows are 128 bytes)
-__device__ __forceinline__ int lds_chunk_off(int r, int c) { return r * 128 + ((c ^ (r & 7)) << 4); }
-
-template <int BM, int BN, int BK, int WM, int WN, bool kSwiglu>
-__global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
-    const uint16_t *__restrict__ A, int64_t M, int Kdim, int Ndim,
-    const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
-    uint16_t *__restrict__ C, const TileTableHeader *__restrict__ hdr,
-    const TileEntry *__restrict__ table, int patch)
-{
-    using Cfg = GemmCfg<BM, BN, BK, WM, WN, kSwiglu>;
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    const int L = tile_of_workgroup(blockIdx.x, patch);
-    if (L >= hdr->num_tiles)
-        return;
-    const TileEntry te = table[L];
-    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-    const int wm = wave / WN, wn = wave % WN;
-
-    constexpr int kStageBytes = (BM + BN) * BK * 2, kATileBytes = BM * BK * 2;
-    auto ldsA = [&](int buf) { return lds + buf * kStageBytes; };
-    auto ldsB = [&](int buf) { return lds + buf * kStageBytes + kATileBytes; };
-
-    // ---- global source pointers of this thread's chunks (advance by BK per K tile)
-    const uint16_t *a_src[Cfg::kAChunks];
-    int a_dst[Cfg::kAChunks];
-#pragma unroll
-    for (int i = 0; i < Cfg::kAChunks; ++i) {
-        const int q = tid + i * Cfg::kThreads;
-        const int r = q / 8, c = q % 8;
-        int64_t m = (int64_t)te.m0 + r;
-        if (m >= te.m_end)
-            m = te.m_end - 1; // rows past the segment repeat its last row; never stored
-        a_src[i] = A + m * Kdim + c * 8;
-        a_dst[i] = lds_chunk_off(r, c);
-    }
-    const uint16_t *b_src[Cfg::kBChunks];
-    int b_dst[Cfg::kBChunks];
-    const int n0 = te.n_tile * Cfg::kOutCols;
-#pragma unroll
-    for (int i = 0; i < Cfg::kBChunks; ++i) {
-        const int q = tid + i * Cfg::kThreads;
-        const int r = q / 8, c = q % 8;
-        const uint16_t *base = B0;
-        int col;
-        if (kSwiglu) {
-            // LDS B rows of one wavefront: first half gate columns, second half the same up columns
-            const int w = r / Cfg::kWaveN, jj = r % Cfg::kWaveN, half = Cfg::kWaveN / 2;
-            base = (jj < half) ? B0 : B1;
-            col = n0 + w * half + (jj % half);
-        } else {
-            col = n0 + r;
-        }
-        if (col >= Ndim)
-            col = Ndim - 1;
-        b_src[i] = base + ((int64_t)te.expert * Ndim + col) * Kdim + c * 8;
-        b_dst[i] = lds_chunk_off(r, c);
-    }
-
-    f32x16 acc[Cfg::kBlkM][Cfg::kBlkN];
-#pragma unroll
-    for (int i = 0; i < Cfg::kBlkM; ++i)
-#pragma unroll
-        for (int j = 0; j < Cfg::kBlkN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                acc[i][j][r] = 0.0f;
-
-    u32x4 a_stage[Cfg::kAChunks], b_stage[Cfg::kBChunks];
-    const int KT = Kdim / BK;
-
-    auto load_global = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < Cfg::kAChunks; ++i)
-            a_stage[i] = *reinterpret_cast<const u32x4 *>(a_src[i] + (int64_t)kt * BK);
-#pragma unroll
-        for (int i = 0; i < Cfg::kBChunks; ++i)
-            b_stage[i] = *reinterpret_cast<const u32x4 *>(b_src[i] + (int64_t)kt * BK);
-    };
-    auto store_lds = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < Cfg::kAChunks; ++i)
-            *reinterpret_cast<u32x4 *>(ldsA(buf) + a_dst[i]) = a_stage[i];
-#pragma unroll
-        for (int i = 0; i < Cfg::kBChunks; ++i)
-            *reinterpret_cast<u32x4 *>(ldsB(buf) + b_dst[i]) = b_stage[i];
-    };
-
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-
-    const int frag_row = lane % 32, frag_kg = lane / 32;
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT)
-            load_global(kt + 1);
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 af[Cfg::kBlkM], bfr[Cfg::kBlkN];
-#pragma unroll
-            for (int i = 0; i < Cfg::kBlkM; ++i) {
-                const int r = wm * Cfg::kWaveM + i * 32 + frag_row;
-                af[i] = *reinterpret_cast<const bf16x8 *>(ldsA(buf) + lds_chunk_off(r, ks * 2 + frag_kg));
-            }
-#pragma unroll
-            for (int j = 0; j < Cfg::kBlkN; ++j) {
-                const int r = wn * Cfg::kWaveN + j * 32 + frag_row;
-                bfr[j] = *reinterpret_cast<const bf16x8 *>(ldsB(buf) + lds_chunk_off(r, ks * 2 + frag_kg));
-            }
-#pragma unroll
-            for (int i = 0; i < Cfg::kBlkM; ++i)
-#pragma unroll
-                for (int j = 0; j < Cfg::kBlkN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < KT)
-            store_lds(buf ^ 1);
-        __syncthreads();
-    }
-
-    // ---- epilogue: accumulator element (i-block, j-block, reg r) is
-    //      row = 8*(r/4) + 4*(lane/32) + r%4, col = lane%32 of its 32x32 block
-    const int col_in_blk = lane % 32, row_base = (lane / 32) * 4;
-    if (kSwiglu) {
-        constexpr int kHalfBlk = Cfg::kBlkN / 2;
-#pragma unroll
-        for (int i = 0; i < Cfg::kBlkM; ++i)
-#pragma unroll
-            for (int j = 0; j < kHalfBlk; ++j) {
-                const int col = n0 + wn * (Cfg::kWaveN / 2) + j * 32 + col_in_blk;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t m = (int64_t)te.m0 + wm * Cfg::kWaveM + i * 32 + (r / 4) * 8 + row_base + (r % 4);
-                    if (m < te.m_end && col < Ndim)
-                        C[m * Ndim + col] = (uint16_t)f32_to_bf16_bits(silu_mul(acc[i][j][r], acc[i][j + kHalfBlk][r]));
-                }
-            }
-    } else {
-#pragma unroll
-        for (int i = 0; i < Cfg::kBlkM; ++i)
-#pragma unroll
-            for (int j = 0; j < Cfg::kBlkN; ++j) {
-                const int col = n0 + wn * Cfg::kWaveN + j * 32 + col_in_blk;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t m = (int64_t)te.m0 + wm * Cfg::kWaveM + i * 32 + (r / 4) * 8 + row_base + (r % 4);
-                    if (m < te.m_end && col < Ndim)
-                        C[m * Ndim + col] = (uint16_t)f32_to_bf16_bits(acc[i][j][r]);
-                }
-            }
-    }
-}
-
 // ------------------------------------------------------------------------
 // fp32 path (small, correctness-oriented): one thread per output element
 // ------------------------------------------------------------------------
@@ -416,13 +218,13 @@ size_t ffn_workspace_bytes(int64_t M, int64_t H, int64_t F, int E_local, int dty
     return make_plan(M, H, F, E_local).total;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool kSwiglu>
+template <int BM, int BN, int WM, int WN, bool kSwiglu>
 static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const uint16_t *B0,
                         const uint16_t *B1, uint16_t *C, const TileTableHeader *hdr,
                         const TileEntry *table, int max_tiles, int patch, hipStream_t st)
 {
-    using Cfg = GemmCfg<BM, BN, BK, WM, WN, kSwiglu>;
-    auto kern = grouped_gemm_bf16<BM, BN, BK, WM, WN, kSwiglu>;
+    using Cfg = GemmCfg<BM, BN, WM, WN, kSwiglu>;
+    auto kern = grouped_gemm_bf16<BM, BN, WM, WN, kSwiglu>;
     static bool attr_set = false; // raising the dynamic LDS limit is idempotent
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -500,9 +302,9 @@ int launch_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t 
     const uint16_t *xpb = static_cast<const uint16_t *>(xp);
     const uint16_t *wg = static_cast<const uint16_t *>(W_gate), *wu = static_cast<const uint16_t *>(W_up);
     if (p.big)
-        launch_gemm<256, 256, 64, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
+        launch_gemm<256, 256, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
     else
-        launch_gemm<128, 128, 64, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
+        launch_gemm<128, 128, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
     return check_launch("moe_ffn_gate_up");
 }
 
@@ -520,9 +322,9 @@ int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     const uint16_t *wd = static_cast<const uint16_t *>(W_down);
     uint16_t *yb = static_cast<uint16_t *>(y);
     if (p.big)
-        launch_gemm<256, 256, 64, 2, 2, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
+        launch_gemm<256, 256, 2, 2, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
     else
-        launch_gemm<128, 128, 64, 2, 2, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
+        launch_gemm<128, 128, 2, 2, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
     return check_launch("moe_ffn_down");
 }
 

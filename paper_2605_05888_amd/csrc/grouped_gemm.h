@@ -1,0 +1,274 @@
+// bf16 matrix-core grouped GEMM for gfx950: C[m, n] = sum_k A[m, k] * B[e(m), n, k]
+// over ragged row segments described by a device-side tile table.
+//
+// Both operands have k contiguous.  One workgroup = WM x WN wavefronts computes a
+// BM x BN tile; every wavefront owns a (BM/WM) x (BN/WN) sub-tile as 32x32 blocks of
+// v_mfma_f32_32x32x16_bf16.
+//
+// Pipeline (BK = 32 per K tile, 4 LDS stages of (BM+BN) x 32 bf16):
+//   * global -> LDS goes through global_load_lds_dwordx4: no staging registers, no
+//     ds_write.  A wavefront instruction fills 1 KiB = 16 tile rows of 64 bytes;
+//     the 16-byte chunk a lane fetches is chosen so that the LDS image is XOR
+//     swizzled and the 16-byte operand reads are bank-conflict free.
+//   * iteration kt:   read operands of (kt, k-step 1)      | 16 MFMA on (kt, k-step 0)
+//                     wait for tile kt+1, ONE barrier,
+//                     issue the loads of tile kt+3,
+//                     read operands of (kt+1, k-step 0)    | 16 MFMA on (kt, k-step 1)
+//     so LDS reads and the three-tile-deep global prefetch always run under MFMAs.
+//     The loads of tile kt+3 overwrite the stage of tile kt-1, which every
+//     wavefront finished reading before it reached this iteration's barrier.
+//   * The matrix-core operands are swapped (weights as the "A" operand), so a lane
+//     ends up with 4 consecutive output columns of one row per accumulator
+//     quadruple and stores them as one 8-byte vector.
+//   * kSwiglu: the B tile holds BN/2 gate rows and the same BN/2 up rows, arranged
+//     so that each wavefront has matching gate/up blocks; the epilogue writes
+//     silu(g)*u, so g and u never reach memory.
+#pragma once
+
+#include "common.h"
+
+namespace moe {
+
+struct TileEntry {
+    int32_t expert; // local expert
+    int32_t m0;     // first row of the tile
+    int32_t m_end;  // end of the expert's segment (rows >= m_end are not written)
+    int32_t n_tile; // column tile
+};
+
+struct TileTableHeader {
+    int32_t num_tiles;
+    int32_t pad[3];
+};
+
+constexpr int kXcds = 8;
+constexpr int kBK = 32;      // K elements per tile
+constexpr int kStages = 4;   // LDS stages
+
+// Workgroup id -> position in the tile order.  Ids are dealt round-robin to the
+// 8 XCDs; each XCD takes runs of `patch` consecutive tiles so its L2 sees tiles
+// that share weight and activation rows.
+__device__ __forceinline__ int tile_of_workgroup(int id, int patch)
+{
+    const int xcd = id % kXcds, j = id / kXcds;
+    return (j / patch) * (patch * kXcds) + xcd * patch + (j % patch);
+}
+
+__device__ __forceinline__ float silu_mul(float g, float u)
+{
+    return g / (1.0f + __expf(-g)) * u;
+}
+
+// XOR key of a 64-byte tile row: any 8 and any 16 consecutive rows spread their
+// equal logical chunks over all banks.
+__device__ __forceinline__ int row_key(int r) { return (((r >> 1) ^ (r >> 3)) & 1) | ((r >> 1) & 2); }
+
+// s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt = [15:14][3:0], expcnt [6:4], lgkmcnt [11:8])
+#define MOE_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+
+// Workgroup barrier without the memory fence of __syncthreads (a fence would drain the
+// outstanding global->LDS loads of the tiles still in flight).  The empty asm statements keep
+// the compiler from moving LDS accesses across it.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <int BM, int BN, int WM, int WN, bool kSwiglu>
+struct GemmCfg {
+    static constexpr int kWaves = WM * WN;
+    static constexpr int kThreads = kWaves * kWave;
+    static constexpr int kWaveM = BM / WM;    // rows per wavefront
+    static constexpr int kWaveN = BN / WN;    // LDS B rows per wavefront
+    static constexpr int kBlkM = kWaveM / 32; // 32x32 blocks per wavefront
+    static constexpr int kBlkN = kWaveN / 32;
+    static constexpr int kAGroups = BM / 16 / kWaves; // 16-row load groups per wavefront
+    static constexpr int kBGroups = BN / 16 / kWaves;
+    static constexpr int kLoadsPerTile = kAGroups + kBGroups; // per lane, per K tile
+    static constexpr int kOutCols = kSwiglu ? BN / 2 : BN;
+    static constexpr int kATileBytes = BM * kBK * 2;
+    static constexpr int kStageBytes = (BM + BN) * kBK * 2;
+    static constexpr size_t kLdsBytes = (size_t)kStages * kStageBytes;
+    static_assert(kWaveM % 32 == 0 && kWaveN % 32 == 0, "wave tile must be 32x32 blocks");
+    static_assert(BM % (16 * kWaves) == 0 && BN % (16 * kWaves) == 0, "load groups");
+    static_assert(!kSwiglu || kBlkN % 2 == 0, "gate and up halves");
+    static_assert(kLoadsPerTile <= 15, "vmcnt budget");
+};
+
+template <int BM, int BN, int WM, int WN, bool kSwiglu>
+__global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
+    const uint16_t *__restrict__ A, int64_t M, int Kdim, int Ndim,
+    const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
+    uint16_t *__restrict__ C, const TileTableHeader *__restrict__ hdr,
+    const TileEntry *__restrict__ table, int patch)
+{
+    using Cfg = GemmCfg<BM, BN, WM, WN, kSwiglu>;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    const int L = tile_of_workgroup(blockIdx.x, patch);
+    if (L >= hdr->num_tiles)
+        return;
+    const TileEntry te = table[L];
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int wm = wave / WN, wn = wave % WN;
+    const int n0 = te.n_tile * Cfg::kOutCols;
+
+    // ---- global->LDS loads: lane fetches chunk (lane%4 ^ key) of row lane/4 of its 16-row group
+    const int ld_row = lane / 4, ld_pc = lane % 4;
+    const uint16_t *a_src[Cfg::kAGroups];
+#pragma unroll
+    for (int g = 0; g < Cfg::kAGroups; ++g) {
+        const int r = (wave * Cfg::kAGroups + g) * 16 + ld_row;
+        int64_t m = (int64_t)te.m0 + r;
+        if (m >= te.m_end)
+            m = te.m_end - 1; // rows past the segment repeat its last row; never stored
+        a_src[g] = A + m * Kdim + ((ld_pc ^ row_key(r)) * 8);
+    }
+    const uint16_t *b_src[Cfg::kBGroups];
+#pragma unroll
+    for (int g = 0; g < Cfg::kBGroups; ++g) {
+        const int r = (wave * Cfg::kBGroups + g) * 16 + ld_row;
+        const uint16_t *base = B0;
+        int col;
+        if (kSwiglu) {
+            // B rows of one wavefront: first half gate columns, second half the same up columns
+            const int w = r / Cfg::kWaveN, jj = r % Cfg::kWaveN, half = Cfg::kWaveN / 2;
+            base = (jj < half) ? B0 : B1;
+            col = n0 + w * half + (jj % half);
+        } else {
+            col = n0 + r;
+        }
+        if (col >= Ndim)
+            col = Ndim - 1;
+        b_src[g] = base + ((int64_t)te.expert * Ndim + col) * Kdim + ((ld_pc ^ row_key(r)) * 8);
+    }
+    const int KT = Kdim / kBK;
+
+    auto issue_tile = [&](int kt) {
+        unsigned char *stage = lds + (kt % kStages) * Cfg::kStageBytes;
+#pragma unroll
+        for (int g = 0; g < Cfg::kAGroups; ++g)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(a_src[g] + (int64_t)kt * kBK),
+                (__attribute__((address_space(3))) void *)(stage + (wave * Cfg::kAGroups + g) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int g = 0; g < Cfg::kBGroups; ++g)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(b_src[g] + (int64_t)kt * kBK),
+                (__attribute__((address_space(3))) void *)(stage + Cfg::kATileBytes + (wave * Cfg::kBGroups + g) * 1024),
+                16, 0, 0);
+    };
+
+    // ---- operand reads: lane (i = lane%32, kg = lane/32) reads chunk (2*ks + kg) of row i of a block
+    const int fr = lane % 32, kg = lane / 32;
+    const int key = row_key(fr); // block and wavefront offsets are multiples of 32 rows: same key
+    const int a_off0 = (wm * Cfg::kWaveM + fr) * 64 + ((kg ^ key) << 4);
+    const int b_off0 = Cfg::kATileBytes + (wn * Cfg::kWaveN + fr) * 64 + ((kg ^ key) << 4);
+    // k-step 1 reads chunk (2 + kg): same offsets with chunk bit 1 flipped
+    const int a_off1 = a_off0 ^ 32, b_off1 = b_off0 ^ 32;
+
+    bf16x8 fa[2][Cfg::kBlkM], fb[2][Cfg::kBlkN];
+    auto read_frags = [&](int kt, int ks, int slot) {
+        const unsigned char *stage = lds + (kt % kStages) * Cfg::kStageBytes;
+        const unsigned char *pa = stage + (ks ? a_off1 : a_off0);
+        const unsigned char *pb = stage + (ks ? b_off1 : b_off0);
+#pragma unroll
+        for (int i = 0; i < Cfg::kBlkM; ++i)
+            fa[slot][i] = *reinterpret_cast<const bf16x8 *>(pa + i * 32 * 64);
+#pragma unroll
+        for (int j = 0; j < Cfg::kBlkN; ++j)
+            fb[slot][j] = *reinterpret_cast<const bf16x8 *>(pb + j * 32 * 64);
+    };
+
+    f32x16 acc[Cfg::kBlkM][Cfg::kBlkN];
+#pragma unroll
+    for (int i = 0; i < Cfg::kBlkM; ++i)
+#pragma unroll
+        for (int j = 0; j < Cfg::kBlkN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[i][j][r] = 0.0f;
+
+    auto mfma_all = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < Cfg::kBlkM; ++i)
+#pragma unroll
+            for (int j = 0; j < Cfg::kBlkN; ++j) // weights first: the result block is [n][m]
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
+    };
+
+    // ---- prologue: three tiles in flight, tile 0 landed
+    issue_tile(0);
+    if (KT > 1)
+        issue_tile(1);
+    if (KT > 2)
+        issue_tile(2);
+    if (KT > 2)
+        MOE_WAIT_VMCNT(2 * Cfg::kLoadsPerTile);
+    else if (KT > 1)
+        MOE_WAIT_VMCNT(Cfg::kLoadsPerTile);
+    else
+        MOE_WAIT_VMCNT(0);
+    lds_barrier();
+    read_frags(0, 0, 0);
+
+    // steady state: every step exists, so the body is branch free (a branch around the LDS
+    // reads would make the compiler wait for them before the MFMAs that do not need them)
+    int kt = 0;
+    for (; kt + 3 < KT; ++kt) {
+        read_frags(kt, 1, 1);
+        mfma_all(0);
+        MOE_WAIT_VMCNT(Cfg::kLoadsPerTile); // tile kt+1 landed (own loads); tile kt+2 may be in flight
+        lds_barrier();                      // ... and everyone's
+        issue_tile(kt + 3);
+        read_frags(kt + 1, 0, 0);
+        mfma_all(1);
+    }
+    // last three tiles: nothing left to issue
+    for (; kt < KT; ++kt) {
+        read_frags(kt, 1, 1);
+        mfma_all(0);
+        if (kt + 2 < KT)
+            MOE_WAIT_VMCNT(Cfg::kLoadsPerTile);
+        else
+            MOE_WAIT_VMCNT(0);
+        lds_barrier();
+        read_frags(kt + 1 < KT ? kt + 1 : kt, 0, 0); // the last one re-reads a valid stage; unused
+        mfma_all(1);
+    }
+
+    // ---- epilogue.  Block (i, j), register r of lane l:
+    //      output row    m = i*32 + l%32               (within the wavefront's rows)
+    //      output column n = j*32 + 8*(r/4) + 4*(l/32) + r%4
+    const int m_lane = lane % 32, n_lane = (lane / 32) * 4;
+    constexpr int kOutBlkN = kSwiglu ? Cfg::kBlkN / 2 : Cfg::kBlkN;
+#pragma unroll
+    for (int i = 0; i < Cfg::kBlkM; ++i) {
+        const int64_t m = (int64_t)te.m0 + wm * Cfg::kWaveM + i * 32 + m_lane;
+        if (m >= te.m_end)
+            continue;
+        uint16_t *crow = C + m * Ndim;
+#pragma unroll
+        for (int j = 0; j < kOutBlkN; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int col = n0 + wn * (kOutBlkN * 32) + j * 32 + q * 8 + n_lane;
+                if (col >= Ndim)
+                    continue;
+                float v[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    v[t] = kSwiglu ? silu_mul(acc[i][j][q * 4 + t], acc[i][j + kOutBlkN][q * 4 + t])
+                                   : acc[i][j][q * 4 + t];
+                u32x2 o;
+                o[0] = pack_bf16x2(v[0], v[1]);
+                o[1] = pack_bf16x2(v[2], v[3]);
+                *reinterpret_cast<u32x2 *>(crow + col) = o;
+            }
+        }
+    }
+}
+
+}  // namespace moe
