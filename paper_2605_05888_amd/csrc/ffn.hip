@@ -16,6 +16,8 @@
 // together share weight tiles; workgroup ids are spread so that each XCD's L2
 // sees a compact patch of that order.  Nothing about the routing result is read
 // on the host.
+#include <stdlib.h>
+
 #include "common.h"
 #include "grouped_gemm.h"
 
@@ -218,13 +220,13 @@ size_t ffn_workspace_bytes(int64_t M, int64_t H, int64_t F, int E_local, int dty
     return make_plan(M, H, F, E_local).total;
 }
 
-template <int BM, int BN, int WM, int WN, bool kSwiglu>
+template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK = 32, int kStages = 4>
 static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const uint16_t *B0,
                         const uint16_t *B1, uint16_t *C, const TileTableHeader *hdr,
                         const TileEntry *table, int max_tiles, int patch, hipStream_t st)
 {
-    using Cfg = GemmCfg<BM, BN, WM, WN, kSwiglu>;
-    auto kern = grouped_gemm_bf16<BM, BN, WM, WN, kSwiglu>;
+    using Cfg = GemmCfg<BM, BN, WM, WN, kSwiglu, kBK, kStages>;
+    auto kern = grouped_gemm_bf16<BM, BN, WM, WN, kSwiglu, kBK, kStages>;
     static bool attr_set = false; // raising the dynamic LDS limit is idempotent
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -268,7 +270,6 @@ static FfnWorkspace carve(const FfnPlan &p, void *ws)
     return k;
 }
 
-constexpr int kPatch = 32;
 
 int launch_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
                         const int32_t *seg_offsets, void *ws, hipStream_t st)
@@ -301,7 +302,17 @@ int launch_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t 
     const FfnWorkspace k = carve(p, ws);
     const uint16_t *xpb = static_cast<const uint16_t *>(xp);
     const uint16_t *wg = static_cast<const uint16_t *>(W_gate), *wu = static_cast<const uint16_t *>(W_up);
-    if (p.big)
+    static const int variant = getenv("MOE_GEMM_VARIANT") ? atoi(getenv("MOE_GEMM_VARIANT")) : 0;
+    static const int kPatch = getenv("MOE_GEMM_PATCH") ? atoi(getenv("MOE_GEMM_PATCH")) : 32;
+    if (p.big && variant == 1)
+        launch_gemm<256, 256, 2, 4, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
+    else if (p.big && variant == 2)
+        launch_gemm<256, 256, 2, 2, true, 64, 2>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
+    else if (p.big && variant == 3)
+        launch_gemm<256, 256, 2, 4, true, 64, 2>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
+    else if (p.big && variant == 4)
+        launch_gemm<256, 256, 2, 2, true, 32, 3>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
+    else if (p.big)
         launch_gemm<256, 256, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
     else
         launch_gemm<128, 128, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
@@ -321,7 +332,17 @@ int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     const FfnWorkspace k = carve(p, ws);
     const uint16_t *wd = static_cast<const uint16_t *>(W_down);
     uint16_t *yb = static_cast<uint16_t *>(y);
-    if (p.big)
+    static const int variant = getenv("MOE_GEMM_VARIANT") ? atoi(getenv("MOE_GEMM_VARIANT")) : 0;
+    static const int kPatch = getenv("MOE_GEMM_PATCH") ? atoi(getenv("MOE_GEMM_PATCH")) : 32;
+    if (p.big && variant == 1)
+        launch_gemm<256, 256, 2, 4, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
+    else if (p.big && variant == 2)
+        launch_gemm<256, 256, 2, 2, false, 64, 2>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
+    else if (p.big && variant == 3)
+        launch_gemm<256, 256, 2, 4, false, 64, 2>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
+    else if (p.big && variant == 4)
+        launch_gemm<256, 256, 2, 2, false, 32, 3>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
+    else if (p.big)
         launch_gemm<256, 256, 2, 2, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
     else
         launch_gemm<128, 128, 2, 2, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);

@@ -5,18 +5,19 @@
 // BM x BN tile; every wavefront owns a (BM/WM) x (BN/WN) sub-tile as 32x32 blocks of
 // v_mfma_f32_32x32x16_bf16.
 //
-// Pipeline (BK = 32 per K tile, 4 LDS stages of (BM+BN) x 32 bf16):
+// Pipeline (K tiles of BK = 32 or 64 elements, S LDS stages of (BM+BN) x BK bf16):
 //   * global -> LDS goes through global_load_lds_dwordx4: no staging registers, no
-//     ds_write.  A wavefront instruction fills 1 KiB = 16 tile rows of 64 bytes;
-//     the 16-byte chunk a lane fetches is chosen so that the LDS image is XOR
-//     swizzled and the 16-byte operand reads are bank-conflict free.
-//   * iteration kt:   read operands of (kt, k-step 1)      | 16 MFMA on (kt, k-step 0)
-//                     wait for tile kt+1, ONE barrier,
-//                     issue the loads of tile kt+3,
-//                     read operands of (kt+1, k-step 0)    | 16 MFMA on (kt, k-step 1)
-//     so LDS reads and the three-tile-deep global prefetch always run under MFMAs.
-//     The loads of tile kt+3 overwrite the stage of tile kt-1, which every
-//     wavefront finished reading before it reached this iteration's barrier.
+//     ds_write.  A wavefront instruction fills 1 KiB of consecutive tile rows; the
+//     16-byte chunk a lane fetches is chosen so that the LDS image is XOR swizzled
+//     and the 16-byte operand reads are bank-conflict free.
+//   * a K tile is BK/16 k-steps of 16 MFMAs (for a 128x128 wavefront tile).  The
+//     operands of k-step ks+1 are read from LDS while the MFMAs of ks run.  Before
+//     the last k-step of tile kt there is ONE barrier: by then every wavefront has
+//     read all of tile kt, and tile kt+1 has landed (own loads: vmcnt, everyone's:
+//     the barrier).  After it the loads of tile kt+S go into the stage tile kt just
+//     left and the first operands of tile kt+1 are read, both under the MFMAs of
+//     the last k-step.  So S tiles are in flight or in use at any time and neither
+//     LDS latency nor the global prefetch is exposed.
 //   * The matrix-core operands are swapped (weights as the "A" operand), so a lane
 //     ends up with 4 consecutive output columns of one row per accumulator
 //     quadruple and stores them as one 8-byte vector.
@@ -42,8 +43,6 @@ struct TileTableHeader {
 };
 
 constexpr int kXcds = 8;
-constexpr int kBK = 32;      // K elements per tile
-constexpr int kStages = 4;   // LDS stages
 
 // Workgroup id -> position in the tile order.  Ids are dealt round-robin to the
 // 8 XCDs; each XCD takes runs of `patch` consecutive tiles so its L2 sees tiles
@@ -59,12 +58,36 @@ __device__ __forceinline__ float silu_mul(float g, float u)
     return g / (1.0f + __expf(-g)) * u;
 }
 
-// XOR key of a 64-byte tile row: any 8 and any 16 consecutive rows spread their
-// equal logical chunks over all banks.
-__device__ __forceinline__ int row_key(int r) { return (((r >> 1) ^ (r >> 3)) & 1) | ((r >> 1) & 2); }
+// XOR key of a tile row with kChunks 16-byte chunks: equal logical chunks of any 8 and
+// of any 16 consecutive rows land in different banks, whether the LDS serves 128 or 256
+// bytes per clock.
+template <int kChunks>
+__device__ __forceinline__ int row_key(int r)
+{
+    if (kChunks == 8) // 128-byte rows
+        return ((r ^ (r >> 3)) & 1) | (r & 6);
+    return (((r >> 1) ^ (r >> 3)) & 1) | ((r >> 1) & 2); // 64-byte rows
+}
 
 // s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt = [15:14][3:0], expcnt [6:4], lgkmcnt [11:8])
 #define MOE_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+// s_waitcnt lgkmcnt(0) only
+#define MOE_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
+
+// Waits until at most `tiles` K tiles (kLoads loads each) of this lane are still in flight;
+// `tiles` is clamped to [0, kMax].
+template <int kLoads, int kMax>
+__device__ __forceinline__ void wait_tiles_in_flight(int tiles)
+{
+    if constexpr (kMax <= 0) {
+        MOE_WAIT_VMCNT(0);
+    } else {
+        if (tiles >= kMax)
+            MOE_WAIT_VMCNT(kMax * kLoads);
+        else
+            wait_tiles_in_flight<kLoads, kMax - 1>(tiles);
+    }
+}
 
 // Workgroup barrier without the memory fence of __syncthreads (a fence would drain the
 // outstanding global->LDS loads of the tiles still in flight).  The empty asm statements keep
@@ -76,7 +99,28 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("" ::: "memory");
 }
 
-template <int BM, int BN, int WM, int WN, bool kSwiglu>
+// Scheduling hint for one k-step: start with an MFMA, then alternate the kReads LDS reads
+// (and, after the barrier, the kLoads global->LDS loads) with MFMAs so that they all issue
+// early under the matrix pipe, and finish with the remaining MFMAs.
+template <int kMfma, int kReads, int kLoads>
+__device__ __forceinline__ void interleave_under_mfma()
+{
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0); // VMEM read
+    }
+#pragma unroll
+    for (int i = 0; i < kReads; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // DS read
+    }
+    constexpr int kRest = kMfma - kReads - kLoads;
+    if constexpr (kRest > 0)
+        __builtin_amdgcn_sched_group_barrier(0x008, kRest, 0);
+}
+
+template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK, int kStages>
 struct GemmCfg {
     static constexpr int kWaves = WM * WN;
     static constexpr int kThreads = kWaves * kWave;
@@ -84,27 +128,36 @@ struct GemmCfg {
     static constexpr int kWaveN = BN / WN;    // LDS B rows per wavefront
     static constexpr int kBlkM = kWaveM / 32; // 32x32 blocks per wavefront
     static constexpr int kBlkN = kWaveN / 32;
-    static constexpr int kAGroups = BM / 16 / kWaves; // 16-row load groups per wavefront
-    static constexpr int kBGroups = BN / 16 / kWaves;
+    static constexpr int kRowBytes = kBK * 2;
+    static constexpr int kChunks = kRowBytes / 16;       // 16-byte chunks per tile row
+    static constexpr int kGroupRows = 1024 / kRowBytes;  // rows one wavefront load instruction fills
+    static constexpr int kAGroups = BM / kGroupRows / kWaves;
+    static constexpr int kBGroups = BN / kGroupRows / kWaves;
     static constexpr int kLoadsPerTile = kAGroups + kBGroups; // per lane, per K tile
+    static constexpr int kKSteps = kBK / 16;
+    static constexpr int kMfmaPerStep = kBlkM * kBlkN;
+    static constexpr int kReadsPerStep = kBlkM + kBlkN;
     static constexpr int kOutCols = kSwiglu ? BN / 2 : BN;
-    static constexpr int kATileBytes = BM * kBK * 2;
-    static constexpr int kStageBytes = (BM + BN) * kBK * 2;
+    static constexpr int kATileBytes = BM * kRowBytes;
+    static constexpr int kStageBytes = (BM + BN) * kRowBytes;
     static constexpr size_t kLdsBytes = (size_t)kStages * kStageBytes;
+    static_assert(kBK == 32 || kBK == 64, "K tile");
+    static_assert(kStages >= 2, "stages");
     static_assert(kWaveM % 32 == 0 && kWaveN % 32 == 0, "wave tile must be 32x32 blocks");
-    static_assert(BM % (16 * kWaves) == 0 && BN % (16 * kWaves) == 0, "load groups");
+    static_assert(BM % (kGroupRows * kWaves) == 0 && BN % (kGroupRows * kWaves) == 0, "load groups");
     static_assert(!kSwiglu || kBlkN % 2 == 0, "gate and up halves");
-    static_assert(kLoadsPerTile <= 15, "vmcnt budget");
+    static_assert(kLoadsPerTile * (kStages - 1) <= 63, "vmcnt budget");
 };
 
-template <int BM, int BN, int WM, int WN, bool kSwiglu>
+template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK, int kStages>
 __global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
     const uint16_t *__restrict__ A, int64_t M, int Kdim, int Ndim,
     const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
     uint16_t *__restrict__ C, const TileTableHeader *__restrict__ hdr,
     const TileEntry *__restrict__ table, int patch)
 {
-    using Cfg = GemmCfg<BM, BN, WM, WN, kSwiglu>;
+    using Cfg = GemmCfg<BM, BN, WM, WN, kSwiglu, kBK, kStages>;
+    constexpr int kChunks = Cfg::kChunks, kRowBytes = Cfg::kRowBytes, kKSteps = Cfg::kKSteps;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int L = tile_of_workgroup(blockIdx.x, patch);
     if (L >= hdr->num_tiles)
@@ -115,21 +168,21 @@ __global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
     const int wm = wave / WN, wn = wave % WN;
     const int n0 = te.n_tile * Cfg::kOutCols;
 
-    // ---- global->LDS loads: lane fetches chunk (lane%4 ^ key) of row lane/4 of its 16-row group
-    const int ld_row = lane / 4, ld_pc = lane % 4;
+    // ---- global->LDS loads: the lane at 16-byte position p of its row fetches chunk p ^ key(row)
+    const int ld_row = lane / kChunks, ld_pc = lane % kChunks;
     const uint16_t *a_src[Cfg::kAGroups];
 #pragma unroll
     for (int g = 0; g < Cfg::kAGroups; ++g) {
-        const int r = (wave * Cfg::kAGroups + g) * 16 + ld_row;
+        const int r = (wave * Cfg::kAGroups + g) * Cfg::kGroupRows + ld_row;
         int64_t m = (int64_t)te.m0 + r;
         if (m >= te.m_end)
             m = te.m_end - 1; // rows past the segment repeat its last row; never stored
-        a_src[g] = A + m * Kdim + ((ld_pc ^ row_key(r)) * 8);
+        a_src[g] = A + m * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8);
     }
     const uint16_t *b_src[Cfg::kBGroups];
 #pragma unroll
     for (int g = 0; g < Cfg::kBGroups; ++g) {
-        const int r = (wave * Cfg::kBGroups + g) * 16 + ld_row;
+        const int r = (wave * Cfg::kBGroups + g) * Cfg::kGroupRows + ld_row;
         const uint16_t *base = B0;
         int col;
         if (kSwiglu) {
@@ -142,7 +195,7 @@ __global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
         }
         if (col >= Ndim)
             col = Ndim - 1;
-        b_src[g] = base + ((int64_t)te.expert * Ndim + col) * Kdim + ((ld_pc ^ row_key(r)) * 8);
+        b_src[g] = base + ((int64_t)te.expert * Ndim + col) * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8);
     }
     const int KT = Kdim / kBK;
 
@@ -161,25 +214,25 @@ __global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
                 16, 0, 0);
     };
 
-    // ---- operand reads: lane (i = lane%32, kg = lane/32) reads chunk (2*ks + kg) of row i of a block
+    // ---- operand reads: lane (i = lane%32, kg = lane/32) reads chunk (2*ks + kg) of row i of a block.
+    //      Block and wavefront offsets are multiples of 32 rows, so the key depends on i only, and
+    //      k-step ks is the k-step-0 offset with chunk bits flipped by 2*ks.
     const int fr = lane % 32, kg = lane / 32;
-    const int key = row_key(fr); // block and wavefront offsets are multiples of 32 rows: same key
-    const int a_off0 = (wm * Cfg::kWaveM + fr) * 64 + ((kg ^ key) << 4);
-    const int b_off0 = Cfg::kATileBytes + (wn * Cfg::kWaveN + fr) * 64 + ((kg ^ key) << 4);
-    // k-step 1 reads chunk (2 + kg): same offsets with chunk bit 1 flipped
-    const int a_off1 = a_off0 ^ 32, b_off1 = b_off0 ^ 32;
+    const int key = row_key<kChunks>(fr);
+    const int a_off0 = (wm * Cfg::kWaveM + fr) * kRowBytes + ((kg ^ key) << 4);
+    const int b_off0 = Cfg::kATileBytes + (wn * Cfg::kWaveN + fr) * kRowBytes + ((kg ^ key) << 4);
 
     bf16x8 fa[2][Cfg::kBlkM], fb[2][Cfg::kBlkN];
     auto read_frags = [&](int kt, int ks, int slot) {
         const unsigned char *stage = lds + (kt % kStages) * Cfg::kStageBytes;
-        const unsigned char *pa = stage + (ks ? a_off1 : a_off0);
-        const unsigned char *pb = stage + (ks ? b_off1 : b_off0);
+        const unsigned char *pa = stage + (a_off0 ^ (ks << 5));
+        const unsigned char *pb = stage + (b_off0 ^ (ks << 5));
 #pragma unroll
         for (int i = 0; i < Cfg::kBlkM; ++i)
-            fa[slot][i] = *reinterpret_cast<const bf16x8 *>(pa + i * 32 * 64);
+            fa[slot][i] = *reinterpret_cast<const bf16x8 *>(pa + i * 32 * kRowBytes);
 #pragma unroll
         for (int j = 0; j < Cfg::kBlkN; ++j)
-            fb[slot][j] = *reinterpret_cast<const bf16x8 *>(pb + j * 32 * 64);
+            fb[slot][j] = *reinterpret_cast<const bf16x8 *>(pb + j * 32 * kRowBytes);
     };
 
     f32x16 acc[Cfg::kBlkM][Cfg::kBlkN];
@@ -199,44 +252,46 @@ __global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
     };
 
-    // ---- prologue: three tiles in flight, tile 0 landed
-    issue_tile(0);
-    if (KT > 1)
-        issue_tile(1);
-    if (KT > 2)
-        issue_tile(2);
-    if (KT > 2)
-        MOE_WAIT_VMCNT(2 * Cfg::kLoadsPerTile);
-    else if (KT > 1)
-        MOE_WAIT_VMCNT(Cfg::kLoadsPerTile);
-    else
-        MOE_WAIT_VMCNT(0);
+    // ---- prologue: kStages tiles in flight, tile 0 landed
+#pragma unroll
+    for (int t = 0; t < kStages; ++t)
+        if (t < KT)
+            issue_tile(t);
+    wait_tiles_in_flight<Cfg::kLoadsPerTile, kStages - 1>((KT < kStages ? KT : kStages) - 1); // all but tile 0
     lds_barrier();
     read_frags(0, 0, 0);
 
     // steady state: every step exists, so the body is branch free (a branch around the LDS
-    // reads would make the compiler wait for them before the MFMAs that do not need them)
+    // reads would make the compiler wait for them before MFMAs that do not need them)
     int kt = 0;
-    for (; kt + 3 < KT; ++kt) {
-        read_frags(kt, 1, 1);
-        mfma_all(0);
-        MOE_WAIT_VMCNT(Cfg::kLoadsPerTile); // tile kt+1 landed (own loads); tile kt+2 may be in flight
-        lds_barrier();                      // ... and everyone's
-        issue_tile(kt + 3);
+    for (; kt + kStages < KT; ++kt) {
+#pragma unroll
+        for (int ks = 0; ks + 1 < kKSteps; ++ks) {
+            read_frags(kt, ks + 1, (ks + 1) & 1);
+            mfma_all(ks & 1);
+            interleave_under_mfma<Cfg::kMfmaPerStep, Cfg::kReadsPerStep, 0>();
+        }
+        __builtin_amdgcn_sched_barrier(0);                   // keep this k-step's MFMAs above the waits
+        MOE_WAIT_LGKM0();                                    // my reads of tile kt are complete
+        MOE_WAIT_VMCNT((kStages - 2) * Cfg::kLoadsPerTile);  // my part of tile kt+1 has landed
+        lds_barrier();                                       // ... and everyone's
+        issue_tile(kt + kStages);                            // into the stage tile kt just left
         read_frags(kt + 1, 0, 0);
-        mfma_all(1);
+        mfma_all((kKSteps - 1) & 1);
+        interleave_under_mfma<Cfg::kMfmaPerStep, Cfg::kReadsPerStep,
+                              (Cfg::kLoadsPerTile + Cfg::kReadsPerStep <= Cfg::kMfmaPerStep ? Cfg::kLoadsPerTile : 0)>();
     }
-    // last three tiles: nothing left to issue
+    // last kStages tiles: nothing left to issue
     for (; kt < KT; ++kt) {
-        read_frags(kt, 1, 1);
-        mfma_all(0);
-        if (kt + 2 < KT)
-            MOE_WAIT_VMCNT(Cfg::kLoadsPerTile);
-        else
-            MOE_WAIT_VMCNT(0);
+#pragma unroll
+        for (int ks = 0; ks + 1 < kKSteps; ++ks) {
+            read_frags(kt, ks + 1, (ks + 1) & 1);
+            mfma_all(ks & 1);
+        }
+        wait_tiles_in_flight<Cfg::kLoadsPerTile, kStages - 2>(KT - 2 - kt); // tiles after kt+1 may stay in flight
         lds_barrier();
         read_frags(kt + 1 < KT ? kt + 1 : kt, 0, 0); // the last one re-reads a valid stage; unused
-        mfma_all(1);
+        mfma_all((kKSteps - 1) & 1);
     }
 
     // ---- epilogue.  Block (i, j), register r of lane l:
