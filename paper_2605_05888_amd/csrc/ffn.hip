@@ -309,7 +309,7 @@ int launch_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t 
     else if (p.big && variant == 2)
         launch_gemm<256, 256, 2, 2, true, 64, 2>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
     else if (p.big && variant == 3)
-        launch_gemm<256, 256, 2, 4, true, 64, 2>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
+        launch_gemm<256, 256, 2, 2, true, 32, 2>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
     else if (p.big && variant == 4)
         launch_gemm<256, 256, 2, 2, true, 32, 3>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
     else if (p.big)
@@ -339,7 +339,7 @@ int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     else if (p.big && variant == 2)
         launch_gemm<256, 256, 2, 2, false, 64, 2>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
     else if (p.big && variant == 3)
-        launch_gemm<256, 256, 2, 4, false, 64, 2>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
+        launch_gemm<256, 256, 2, 2, false, 32, 2>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
     else if (p.big && variant == 4)
         launch_gemm<256, 256, 2, 2, false, 32, 3>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
     else if (p.big)

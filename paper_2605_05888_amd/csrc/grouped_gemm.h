@@ -26,6 +26,8 @@
 //     silu(g)*u, so g and u never reach memory.
 #pragma once
 
+#include <type_traits>
+
 #include "common.h"
 
 namespace moe {
@@ -156,6 +158,7 @@ __global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
     uint16_t *__restrict__ C, const TileTableHeader *__restrict__ hdr,
     const TileEntry *__restrict__ table, int patch)
 {
+#if defined(__HIP_DEVICE_COMPILE__) // the body uses device-only types (buffer resources); the host pass only needs the stub
     using Cfg = GemmCfg<BM, BN, WM, WN, kSwiglu, kBK, kStages>;
     constexpr int kChunks = Cfg::kChunks, kRowBytes = Cfg::kRowBytes, kKSteps = Cfg::kKSteps;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
@@ -168,50 +171,93 @@ __global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
     const int wm = wave / WN, wn = wave % WN;
     const int n0 = te.n_tile * Cfg::kOutCols;
 
-    // ---- global->LDS loads: the lane at 16-byte position p of its row fetches chunk p ^ key(row)
+    // ---- global->LDS loads (buffer_load_dwordx4 ... lds): the lane at 16-byte position p of its
+    //      row fetches chunk p ^ key(row).  Buffer addressing keeps the per-lane part of the address
+    //      in one 32-bit register (row offset inside the tile, fixed for the whole K loop); the tile
+    //      base sits in the scalar resource and the K offset in a scalar register.
     const int ld_row = lane / kChunks, ld_pc = lane % kChunks;
-    const uint16_t *a_src[Cfg::kAGroups];
+    const int64_t rows_left = (int64_t)te.m_end - te.m0; // >= 1
+    const __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(A + (int64_t)te.m0 * Kdim), 0, 0xFFFFFFFFu, 0x00020000);
+    int a_off[Cfg::kAGroups];
 #pragma unroll
     for (int g = 0; g < Cfg::kAGroups; ++g) {
         const int r = (wave * Cfg::kAGroups + g) * Cfg::kGroupRows + ld_row;
-        int64_t m = (int64_t)te.m0 + r;
-        if (m >= te.m_end)
-            m = te.m_end - 1; // rows past the segment repeat its last row; never stored
-        a_src[g] = A + m * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8);
+        const int rr = r < rows_left ? r : (int)rows_left - 1; // rows past the segment repeat its last row; never stored
+        a_off[g] = (rr * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8)) * 2;
     }
-    const uint16_t *b_src[Cfg::kBGroups];
+    // B rows of one wavefront (kSwiglu): first half gate columns, second half the same up columns.
+    // A load group never straddles the two halves, so its resource is wave-uniform.
+    const int cols_left = Ndim - n0; // >= 1
+    const __amdgpu_buffer_rsrc_t rs_b0 = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(B0 + ((int64_t)te.expert * Ndim + n0) * Kdim), 0, 0xFFFFFFFFu, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_b1 = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>((kSwiglu ? B1 : B0) + ((int64_t)te.expert * Ndim + n0) * Kdim), 0, 0xFFFFFFFFu,
+        0x00020000);
+    int b_off[Cfg::kBGroups];
 #pragma unroll
     for (int g = 0; g < Cfg::kBGroups; ++g) {
         const int r = (wave * Cfg::kBGroups + g) * Cfg::kGroupRows + ld_row;
-        const uint16_t *base = B0;
         int col;
         if (kSwiglu) {
-            // B rows of one wavefront: first half gate columns, second half the same up columns
             const int w = r / Cfg::kWaveN, jj = r % Cfg::kWaveN, half = Cfg::kWaveN / 2;
-            base = (jj < half) ? B0 : B1;
-            col = n0 + w * half + (jj % half);
+            col = w * half + (jj % half);
         } else {
-            col = n0 + r;
+            col = r;
         }
-        if (col >= Ndim)
-            col = Ndim - 1;
-        b_src[g] = base + ((int64_t)te.expert * Ndim + col) * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8);
+        if (col >= cols_left)
+            col = cols_left - 1;
+        b_off[g] = (col * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8)) * 2;
     }
     const int KT = Kdim / kBK;
 
-    auto issue_tile = [&](int kt) {
+    // The kLoadsPerTile loads of a tile (A groups, then B groups) are issued in kKSteps parts, one
+    // part under each k-step's MFMAs, so that the four wavefronts never push a whole tile into
+    // the memory pipeline in one burst right after the barrier.
+    constexpr int kPartLoads = Cfg::kLoadsPerTile / kKSteps;
+    static_assert(Cfg::kLoadsPerTile % kKSteps == 0, "loads per part");
+    auto issue_part = [&](int kt, auto part_tag) {
+        constexpr int part = decltype(part_tag)::value;
         unsigned char *stage = lds + (kt % kStages) * Cfg::kStageBytes;
+        const int koff = kt * (kBK * 2);
 #pragma unroll
-        for (int g = 0; g < Cfg::kAGroups; ++g)
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(a_src[g] + (int64_t)kt * kBK),
-                (__attribute__((address_space(3))) void *)(stage + (wave * Cfg::kAGroups + g) * 1024), 16, 0, 0);
-#pragma unroll
-        for (int g = 0; g < Cfg::kBGroups; ++g)
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(b_src[g] + (int64_t)kt * kBK),
-                (__attribute__((address_space(3))) void *)(stage + Cfg::kATileBytes + (wave * Cfg::kBGroups + g) * 1024),
-                16, 0, 0);
+        for (int q = part * kPartLoads; q < (part + 1) * kPartLoads; ++q) {
+            if (q < Cfg::kAGroups) {
+                const int g = q;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    rs_a, (__attribute__((address_space(3))) void *)(stage + (wave * Cfg::kAGroups + g) * 1024), 16,
+                    a_off[g], koff, 0, 0);
+            } else {
+                const int g = q - Cfg::kAGroups;
+                const int r0 = (wave * Cfg::kBGroups + g) * Cfg::kGroupRows; // uniform
+                const bool up = kSwiglu && (r0 % Cfg::kWaveN) >= Cfg::kWaveN / 2;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    up ? rs_b1 : rs_b0,
+                    (__attribute__((address_space(3))) void *)(stage + Cfg::kATileBytes +
+                                                               (wave * Cfg::kBGroups + g) * 1024),
+                    16, b_off[g], koff, 0, 0);
+            }
+        }
+    };
+    auto issue_tile = [&](int kt) {
+        issue_part(kt, std::integral_constant<int, 0>{});
+        if constexpr (kKSteps > 1)
+            issue_part(kt, std::integral_constant<int, 1>{});
+        if constexpr (kKSteps > 2) {
+            issue_part(kt, std::integral_constant<int, 2>{});
+            issue_part(kt, std::integral_constant<int, 3>{});
+        }
+    };
+    // part ks+1 of a tile goes under k-step ks
+    auto issue_part_for_step = [&](int kt, int ks) {
+        if (ks == 0)
+            issue_part(kt, std::integral_constant<int, 1>{});
+        if constexpr (kKSteps > 2) {
+            if (ks == 1)
+                issue_part(kt, std::integral_constant<int, 2>{});
+            if (ks == 2)
+                issue_part(kt, std::integral_constant<int, 3>{});
+        }
     };
 
     // ---- operand reads: lane (i = lane%32, kg = lane/32) reads chunk (2*ks + kg) of row i of a block.
@@ -252,12 +298,17 @@ __global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
     };
 
-    // ---- prologue: kStages tiles in flight, tile 0 landed
+    // ---- prologue: tiles 0 .. kStages-2 and the first part of tile kStages-1 in flight, tile 0 landed
 #pragma unroll
-    for (int t = 0; t < kStages; ++t)
+    for (int t = 0; t + 1 < kStages; ++t)
         if (t < KT)
             issue_tile(t);
-    wait_tiles_in_flight<Cfg::kLoadsPerTile, kStages - 1>((KT < kStages ? KT : kStages) - 1); // all but tile 0
+    if (kStages - 1 < KT)
+        issue_part(kStages - 1, std::integral_constant<int, 0>{});
+    if (KT >= kStages)
+        MOE_WAIT_VMCNT((kStages - 2) * Cfg::kLoadsPerTile + kPartLoads);
+    else
+        wait_tiles_in_flight<Cfg::kLoadsPerTile, kStages - 2>(KT - 1); // all but tile 0
     lds_barrier();
     read_frags(0, 0, 0);
 
@@ -267,24 +318,27 @@ __global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
     for (; kt + kStages < KT; ++kt) {
 #pragma unroll
         for (int ks = 0; ks + 1 < kKSteps; ++ks) {
+            issue_part_for_step(kt + kStages - 1, ks); // rest of the tile begun one iteration ago
             read_frags(kt, ks + 1, (ks + 1) & 1);
             mfma_all(ks & 1);
-            interleave_under_mfma<Cfg::kMfmaPerStep, Cfg::kReadsPerStep, 0>();
+            interleave_under_mfma<Cfg::kMfmaPerStep, Cfg::kReadsPerStep, kPartLoads>();
         }
         __builtin_amdgcn_sched_barrier(0);                   // keep this k-step's MFMAs above the waits
         MOE_WAIT_LGKM0();                                    // my reads of tile kt are complete
         MOE_WAIT_VMCNT((kStages - 2) * Cfg::kLoadsPerTile);  // my part of tile kt+1 has landed
         lds_barrier();                                       // ... and everyone's
-        issue_tile(kt + kStages);                            // into the stage tile kt just left
+        issue_part(kt + kStages, std::integral_constant<int, 0>{}); // into the stage tile kt just left
         read_frags(kt + 1, 0, 0);
         mfma_all((kKSteps - 1) & 1);
-        interleave_under_mfma<Cfg::kMfmaPerStep, Cfg::kReadsPerStep,
-                              (Cfg::kLoadsPerTile + Cfg::kReadsPerStep <= Cfg::kMfmaPerStep ? Cfg::kLoadsPerTile : 0)>();
+        interleave_under_mfma<Cfg::kMfmaPerStep, Cfg::kReadsPerStep, kPartLoads>();
     }
-    // last kStages tiles: nothing left to issue
+    // last kStages tiles: only the rest of the last tile is still to be issued
     for (; kt < KT; ++kt) {
+        const bool rest = kt + kStages - 1 < KT; // true once, for the first of these iterations
 #pragma unroll
         for (int ks = 0; ks + 1 < kKSteps; ++ks) {
+            if (rest)
+                issue_part_for_step(kt + kStages - 1, ks);
             read_frags(kt, ks + 1, (ks + 1) & 1);
             mfma_all(ks & 1);
         }
@@ -324,6 +378,7 @@ __global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
             }
         }
     }
+#endif
 }
 
 }  // namespace moe
