@@ -269,16 +269,21 @@ __global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
     const int b_off0 = Cfg::kATileBytes + (wn * Cfg::kWaveN + fr) * kRowBytes + ((kg ^ key) << 4);
 
     bf16x8 fa[2][Cfg::kBlkM], fb[2][Cfg::kBlkN];
-    auto read_frags = [&](int kt, int ks, int slot) {
+    // `act` = number of this wavefront's 32-row blocks that hold rows of the segment: blocks past
+    // the end of a ragged segment are neither read nor multiplied.
+    auto read_frags = [&](int kt, int ks, int slot, auto act_tag) {
+        constexpr int kAct = decltype(act_tag)::value;
         const unsigned char *stage = lds + (kt % kStages) * Cfg::kStageBytes;
         const unsigned char *pa = stage + (a_off0 ^ (ks << 5));
         const unsigned char *pb = stage + (b_off0 ^ (ks << 5));
 #pragma unroll
-        for (int i = 0; i < Cfg::kBlkM; ++i)
+        for (int i = 0; i < kAct; ++i)
             fa[slot][i] = *reinterpret_cast<const bf16x8 *>(pa + i * 32 * kRowBytes);
+        if constexpr (kAct > 0) {
 #pragma unroll
-        for (int j = 0; j < Cfg::kBlkN; ++j)
-            fb[slot][j] = *reinterpret_cast<const bf16x8 *>(pb + j * 32 * kRowBytes);
+            for (int j = 0; j < Cfg::kBlkN; ++j)
+                fb[slot][j] = *reinterpret_cast<const bf16x8 *>(pb + j * 32 * kRowBytes);
+        }
     };
 
     f32x16 acc[Cfg::kBlkM][Cfg::kBlkN];
@@ -290,62 +295,81 @@ __global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
             for (int r = 0; r < 16; ++r)
                 acc[i][j][r] = 0.0f;
 
-    auto mfma_all = [&](int slot) {
+    auto mfma_all = [&](int slot, auto act_tag) {
+        constexpr int kAct = decltype(act_tag)::value;
 #pragma unroll
-        for (int i = 0; i < Cfg::kBlkM; ++i)
+        for (int i = 0; i < kAct; ++i)
 #pragma unroll
             for (int j = 0; j < Cfg::kBlkN; ++j) // weights first: the result block is [n][m]
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
     };
 
-    // ---- prologue: tiles 0 .. kStages-2 and the first part of tile kStages-1 in flight, tile 0 landed
-#pragma unroll
-    for (int t = 0; t + 1 < kStages; ++t)
-        if (t < KT)
-            issue_tile(t);
-    if (kStages - 1 < KT)
-        issue_part(kStages - 1, std::integral_constant<int, 0>{});
-    if (KT >= kStages)
-        MOE_WAIT_VMCNT((kStages - 2) * Cfg::kLoadsPerTile + kPartLoads);
-    else
-        wait_tiles_in_flight<Cfg::kLoadsPerTile, kStages - 2>(KT - 1); // all but tile 0
-    lds_barrier();
-    read_frags(0, 0, 0);
-
-    // steady state: every step exists, so the body is branch free (a branch around the LDS
-    // reads would make the compiler wait for them before MFMAs that do not need them)
-    int kt = 0;
-    for (; kt + kStages < KT; ++kt) {
-#pragma unroll
-        for (int ks = 0; ks + 1 < kKSteps; ++ks) {
-            issue_part_for_step(kt + kStages - 1, ks); // rest of the tile begun one iteration ago
-            read_frags(kt, ks + 1, (ks + 1) & 1);
-            mfma_all(ks & 1);
-            interleave_under_mfma<Cfg::kMfmaPerStep, Cfg::kReadsPerStep, kPartLoads>();
-        }
-        __builtin_amdgcn_sched_barrier(0);                   // keep this k-step's MFMAs above the waits
-        MOE_WAIT_LGKM0();                                    // my reads of tile kt are complete
-        MOE_WAIT_VMCNT((kStages - 2) * Cfg::kLoadsPerTile);  // my part of tile kt+1 has landed
-        lds_barrier();                                       // ... and everyone's
-        issue_part(kt + kStages, std::integral_constant<int, 0>{}); // into the stage tile kt just left
-        read_frags(kt + 1, 0, 0);
-        mfma_all((kKSteps - 1) & 1);
-        interleave_under_mfma<Cfg::kMfmaPerStep, Cfg::kReadsPerStep, kPartLoads>();
-    }
-    // last kStages tiles: only the rest of the last tile is still to be issued
-    for (; kt < KT; ++kt) {
-        const bool rest = kt + kStages - 1 < KT; // true once, for the first of these iterations
-#pragma unroll
-        for (int ks = 0; ks + 1 < kKSteps; ++ks) {
-            if (rest)
-                issue_part_for_step(kt + kStages - 1, ks);
-            read_frags(kt, ks + 1, (ks + 1) & 1);
-            mfma_all(ks & 1);
-        }
-        wait_tiles_in_flight<Cfg::kLoadsPerTile, kStages - 2>(KT - 2 - kt); // tiles after kt+1 may stay in flight
+    auto pipeline = [&](auto act) {
+        constexpr int kAct = decltype(act)::value;
+        // ---- prologue: tiles 0 .. kStages-2 and the first part of tile kStages-1 in flight, tile 0 landed
+    #pragma unroll
+        for (int t = 0; t + 1 < kStages; ++t)
+            if (t < KT)
+                issue_tile(t);
+        if (kStages - 1 < KT)
+            issue_part(kStages - 1, std::integral_constant<int, 0>{});
+        if (KT >= kStages)
+            MOE_WAIT_VMCNT((kStages - 2) * Cfg::kLoadsPerTile + kPartLoads);
+        else
+            wait_tiles_in_flight<Cfg::kLoadsPerTile, kStages - 2>(KT - 1); // all but tile 0
         lds_barrier();
-        read_frags(kt + 1 < KT ? kt + 1 : kt, 0, 0); // the last one re-reads a valid stage; unused
-        mfma_all((kKSteps - 1) & 1);
+        read_frags(0, 0, 0, act);
+
+        // steady state: every step exists, so the body is branch free (a branch around the LDS
+        // reads would make the compiler wait for them before MFMAs that do not need them)
+        int kt = 0;
+        for (; kt + kStages < KT; ++kt) {
+    #pragma unroll
+            for (int ks = 0; ks + 1 < kKSteps; ++ks) {
+                issue_part_for_step(kt + kStages - 1, ks); // rest of the tile begun one iteration ago
+                read_frags(kt, ks + 1, (ks + 1) & 1, act);
+                mfma_all(ks & 1, act);
+                interleave_under_mfma<kAct * Cfg::kBlkN, (kAct ? kAct + Cfg::kBlkN : 0), kPartLoads>();
+            }
+            __builtin_amdgcn_sched_barrier(0);                   // keep this k-step's MFMAs above the waits
+            MOE_WAIT_LGKM0();                                    // my reads of tile kt are complete
+            MOE_WAIT_VMCNT((kStages - 2) * Cfg::kLoadsPerTile);  // my part of tile kt+1 has landed
+            lds_barrier();                                       // ... and everyone's
+            issue_part(kt + kStages, std::integral_constant<int, 0>{}); // into the stage tile kt just left
+            read_frags(kt + 1, 0, 0, act);
+            mfma_all((kKSteps - 1) & 1, act);
+            interleave_under_mfma<kAct * Cfg::kBlkN, (kAct ? kAct + Cfg::kBlkN : 0), kPartLoads>();
+        }
+        // last kStages tiles: only the rest of the last tile is still to be issued
+        for (; kt < KT; ++kt) {
+            const bool rest = kt + kStages - 1 < KT; // true once, for the first of these iterations
+    #pragma unroll
+            for (int ks = 0; ks + 1 < kKSteps; ++ks) {
+                if (rest)
+                    issue_part_for_step(kt + kStages - 1, ks);
+                read_frags(kt, ks + 1, (ks + 1) & 1, act);
+                mfma_all(ks & 1, act);
+            }
+            wait_tiles_in_flight<Cfg::kLoadsPerTile, kStages - 2>(KT - 2 - kt); // tiles after kt+1 may stay in flight
+            lds_barrier();
+            read_frags(kt + 1 < KT ? kt + 1 : kt, 0, 0, act); // the last one re-reads a valid stage; unused
+            mfma_all((kKSteps - 1) & 1, act);
+        }
+    };
+    // rows of the segment inside this wavefront's part of the tile -> active 32-row blocks
+    {
+        const int64_t rows = (int64_t)te.m_end - ((int64_t)te.m0 + wm * Cfg::kWaveM);
+        const int active = rows <= 0 ? 0 : (rows >= Cfg::kWaveM ? Cfg::kBlkM : (int)((rows + 31) / 32));
+        if (active == Cfg::kBlkM)
+            pipeline(std::integral_constant<int, Cfg::kBlkM>{});
+        else if (active == 0)
+            pipeline(std::integral_constant<int, 0>{});
+        else if (active == 1)
+            pipeline(std::integral_constant<int, 1>{});
+        else if (Cfg::kBlkM > 2 && active == 2)
+            pipeline(std::integral_constant<int, (Cfg::kBlkM > 2 ? 2 : 1)>{});
+        else
+            pipeline(std::integral_constant<int, (Cfg::kBlkM > 3 ? 3 : 1)>{});
     }
 
     // ---- epilogue.  Block (i, j), register r of lane l:
