@@ -122,6 +122,170 @@ __global__ __launch_bounds__(kWave *kRouteWaves) void router_logits(
     }
 }
 
+// ------------------------------------------------------------------------
+// Tiled variant of the same sum for E % 4 == 0 (the benchmark shapes): a workgroup of four
+// wavefronts computes 32 tokens x 16 experts.  Every wavefront owns 8 tokens and all 16
+// experts (128 accumulators per lane, lane l = partial l of R64 as above).  K tiles of 128
+// columns are staged in LDS by buffer_load ... lds: the W_r tile (128 rows x 16 experts, shared
+// by the four wavefronts, 16-byte chunks XOR-swizzled so that the per-row reads are conflict
+// free) and each wavefront's own 8 x 128 slice of x.  Two stages; the loads of tile kt+1 run
+// under the multiply-adds of tile kt.  Rows past H and tokens past N come back as zeros from
+// the buffer bounds check; adding a zero product never changes a partial sum (partials start
+// at +0 and can never become -0), so the result is the R64 sum bit for bit.
+// ------------------------------------------------------------------------
+constexpr int kRtTok = 8;        // tokens per wavefront
+constexpr int kRtExp = 16;       // experts per workgroup
+constexpr int kRtK = 128;        // K tile
+constexpr int kRtWaves = 4;
+
+__device__ __forceinline__ int rt_key(int r) { return (((r >> 1) ^ (r >> 3)) & 1) | ((r >> 1) & 2); }
+
+template <bool kBf16>
+__global__ __launch_bounds__(kWave *kRtWaves) void router_logits_tiled(
+    const void *__restrict__ x, int64_t N, int H, const float *__restrict__ W_r,
+    const float *__restrict__ bias, int E, float *__restrict__ logits)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int kXb = kBf16 ? 2 : 4;                  // bytes per x element
+    constexpr int kXRow = kRtK * kXb;                   // bytes of one token row in a tile
+    constexpr int kXTile = kRtTok * kXRow;              // per wavefront
+    constexpr int kWTile = kRtK * kRtExp * 4;           // 8 KiB
+    constexpr int kStage = kWTile + kRtWaves * kXTile;
+    constexpr int kXLoads = kXTile / 1024;              // per wavefront per tile
+    constexpr int kWLoads = kWTile / 1024 / kRtWaves;   // per wavefront per tile
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * kStage];
+    const int lane = threadIdx.x % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int e0 = blockIdx.x * kRtExp;
+    const int64_t n0 = ((int64_t)blockIdx.y * kRtWaves + wave) * kRtTok;
+
+    // W_r tile rows are 64 bytes (16 experts); a load instruction fills 16 rows
+    const int64_t w_bytes = (int64_t)H * E * 4 - (int64_t)e0 * 4;
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(W_r + e0), 0, (unsigned)(w_bytes > 0xFFFFFFFFll ? 0xFFFFFFFFll : w_bytes), 0x00020000);
+    int w_off[kWLoads];
+#pragma unroll
+    for (int g = 0; g < kWLoads; ++g) {
+        const int r = (wave * kWLoads + g) * 16 + lane / 4; // row inside the tile
+        w_off[g] = (r * E + ((lane % 4) ^ rt_key(r)) * 4) * 4;
+    }
+    // x: this wavefront's 8 token rows; a load instruction fills 1024 / kXRow token rows
+    const int64_t n_left = N - n0; // may be <= 0 for the last workgroup: then nothing is in range
+    const int64_t x_bytes = n_left > 0 ? n_left * H * kXb : 0;
+    const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned char *>(static_cast<const unsigned char *>(x) + n0 * H * kXb), 0,
+        (unsigned)(x_bytes > 0xFFFFFFFFll ? 0xFFFFFFFFll : x_bytes), 0x00020000);
+    constexpr int kLanesPerRow = kXRow / 16;
+    int x_off[kXLoads];
+#pragma unroll
+    for (int g = 0; g < kXLoads; ++g) {
+        const int t = g * (kWave / kLanesPerRow) + lane / kLanesPerRow;
+        x_off[g] = (t * H + (lane % kLanesPerRow) * (16 / kXb)) * kXb;
+    }
+    // a column range [k0, k0 + 128) that crosses H would read the next token's row: mask those lanes
+    auto issue = [&](int kt) {
+        unsigned char *st = lds + (kt & 1) * kStage;
+        const int k0 = kt * kRtK;
+#pragma unroll
+        for (int g = 0; g < kWLoads; ++g)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rs_w, (__attribute__((address_space(3))) void *)(st + (wave * kWLoads + g) * 1024), 16,
+                w_off[g], k0 * E * 4, 0, 0);
+#pragma unroll
+        for (int g = 0; g < kXLoads; ++g)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rs_x, (__attribute__((address_space(3))) void *)(st + kWTile + wave * kXTile + g * 1024), 16,
+                x_off[g], k0 * kXb, 0, 0);
+    };
+
+    float acc[kRtTok * kRtExp];
+#pragma unroll
+    for (int i = 0; i < kRtTok * kRtExp; ++i)
+        acc[i] = 0.0f;
+
+    const int KT = (H + kRtK - 1) / kRtK;
+    const int key = rt_key(lane); // rows lane and lane + 64 of a tile share the key bits
+    issue(0);
+    for (int kt = 0; kt < KT; ++kt) {
+        __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): tile kt has landed (own loads)
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();       // ... and everyone's; tile kt-1 is no longer read
+        asm volatile("" ::: "memory");
+        if (kt + 1 < KT)
+            issue(kt + 1);
+        const unsigned char *st = lds + (kt & 1) * kStage;
+        const unsigned char *xs = st + kWTile + wave * kXTile;
+#pragma unroll
+        for (int sub = 0; sub < kRtK / kWave; ++sub) {
+            const int row = sub * kWave + lane; // tile row = column h of this lane
+            float wv[kRtExp];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const f32x4 w4 = *reinterpret_cast<const f32x4 *>(st + row * 64 + ((c ^ key) << 4));
+                wv[4 * c] = w4[0];
+                wv[4 * c + 1] = w4[1];
+                wv[4 * c + 2] = w4[2];
+                wv[4 * c + 3] = w4[3];
+            }
+            float xv[kRtTok];
+#pragma unroll
+            for (int t = 0; t < kRtTok; ++t) {
+                if (kBf16)
+                    xv[t] = bf16_bits_to_f32(*reinterpret_cast<const uint16_t *>(xs + t * kXRow + row * 2));
+                else
+                    xv[t] = *reinterpret_cast<const float *>(xs + t * kXRow + row * 4);
+            }
+            // columns past H: W_r came back as zeros, but x may hold the next row's values; the
+            // products are +-0 either way
+#pragma unroll
+            for (int t = 0; t < kRtTok; ++t)
+#pragma unroll
+                for (int j = 0; j < kRtExp; ++j)
+                    acc[t * kRtExp + j] = fmaf(xv[t], wv[j], acc[t * kRtExp + j]);
+        }
+    }
+
+    // fold the 64 partials of every (token, expert) pair: two groups of 64 pairs (experts 0-7, 8-15)
+    float lo[64], hi[64];
+#pragma unroll
+    for (int t = 0; t < kRtTok; ++t)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            lo[t * 8 + j] = acc[t * kRtExp + j];
+            hi[t * 8 + j] = acc[t * kRtExp + 8 + j];
+        }
+    fold_round<32>(lo, lane & 32);
+    fold_round<32>(hi, lane & 32);
+    fold_round<16>(lo, lane & 16);
+    fold_round<16>(hi, lane & 16);
+    fold_round<8>(lo, lane & 8);
+    fold_round<8>(hi, lane & 8);
+    fold_round<4>(lo, lane & 4);
+    fold_round<4>(hi, lane & 4);
+    fold_round<2>(lo, lane & 2);
+    fold_round<2>(hi, lane & 2);
+    fold_round<1>(lo, lane & 1);
+    fold_round<1>(hi, lane & 1);
+    const int t = lane / 8, j = lane % 8;
+    const int64_t n = n0 + t;
+    if (n < N) {
+        const int ea = e0 + j, eb = e0 + 8 + j;
+        if (ea < E) {
+            float v = lo[0];
+            if (bias)
+                v = v + bias[ea];
+            logits[n * E + ea] = v;
+        }
+        if (eb < E) {
+            float v = hi[0];
+            if (bias)
+                v = v + bias[eb];
+            logits[n * E + eb] = v;
+        }
+    }
+#endif
+}
+
 // (value, index) order of the selection: larger logit first, equal logits to the lower index.
 __device__ __forceinline__ bool better(float va, int ia, float vb, int ib)
 {
@@ -206,11 +370,21 @@ int launch_route(const void *x, int dtype, int64_t N, int64_t H, const float *W_
                  float *topk_w, float *logits, hipStream_t st)
 {
     const dim3 block(kWave * kRouteWaves);
-    const dim3 grid1((unsigned)ceil_div(N, (int64_t)kTok * kRouteWaves), (unsigned)ceil_div(E, kExp));
-    if (dtype == MOE_BF16)
-        hipLaunchKernelGGL(router_logits<true>, grid1, block, 0, st, x, N, H, W_r, bias, E, logits);
-    else
-        hipLaunchKernelGGL(router_logits<false>, grid1, block, 0, st, x, N, H, W_r, bias, E, logits);
+    if (E % 4 == 0 && H * (int64_t)E * 4 < ((int64_t)1 << 31) && H * 8 * 4 < ((int64_t)1 << 31)) {
+        const dim3 grid((unsigned)ceil_div(E, kRtExp), (unsigned)ceil_div(N, (int64_t)kRtTok * kRtWaves));
+        if (dtype == MOE_BF16)
+            hipLaunchKernelGGL(router_logits_tiled<true>, grid, dim3(kWave * kRtWaves), 0, st, x, N, (int)H, W_r,
+                               bias, E, logits);
+        else
+            hipLaunchKernelGGL(router_logits_tiled<false>, grid, dim3(kWave * kRtWaves), 0, st, x, N, (int)H, W_r,
+                               bias, E, logits);
+    } else {
+        const dim3 grid1((unsigned)ceil_div(N, (int64_t)kTok * kRouteWaves), (unsigned)ceil_div(E, kExp));
+        if (dtype == MOE_BF16)
+            hipLaunchKernelGGL(router_logits<true>, grid1, block, 0, st, x, N, H, W_r, bias, E, logits);
+        else
+            hipLaunchKernelGGL(router_logits<false>, grid1, block, 0, st, x, N, H, W_r, bias, E, logits);
+    }
     const dim3 grid2((unsigned)ceil_div(N, kRouteWaves));
     hipLaunchKernelGGL(router_topk, grid2, block, 0, st, logits, N, E, K, score_mode, topk_idx,
                        topk_w);
