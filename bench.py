@@ -218,6 +218,19 @@ def main():
                              "permute_frac": gbs_perm / PEAK_HBM_GBS, "combine_frac": gbs_comb / PEAK_HBM_GBS},
         "step_breakdown_us": us,
     }
+    # achievable copy bandwidth of this machine: plain 1 GiB device-to-device copy (read + write bytes)
+    import moe_inputs.device as mid
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    mid.copy_bytes(dst, src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        mid.copy_bytes(dst, src)
+    c1.record()
+    torch.cuda.synchronize()
+    result["dispatch_combine"]["plain_copy_GBs"] = 5 * 2 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del src, dst
     if args.cpu_seconds > 0:
         result["cpu_baseline"] = cpu_baseline(cfg, layer, args.cpu_seconds)
     print(json.dumps(result))

@@ -37,6 +37,19 @@ def _load():
     return _lib
 
 
+def copy_bytes(dst, src):
+    """Plain device-to-device copy kernel (the yardstick for HBM counters)."""
+    import torch
+    assert dst.is_cuda and src.is_cuda and dst.is_contiguous() and src.is_contiguous()
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size() and nbytes % 16 == 0
+    lib = _load()
+    lib.moe_inputs_copy.restype = ctypes.c_int
+    lib.moe_inputs_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
+    if lib.moe_inputs_copy(dst.data_ptr(), src.data_ptr(), nbytes, torch.cuda.current_stream().cuda_stream) != 0:
+        raise RuntimeError("copy kernel launch failed")
+
+
 def fill_normal(out, seed: int, stream: int, start: int, sigma: float):
     """Fills the contiguous device tensor `out` (bf16 or fp32) with flat elements
     [start, start + out.numel()) of the stream."""

@@ -44,7 +44,27 @@ __global__ void fill_normal(void *out, int bf16, uint64_t key, uint64_t start, u
     }
 }
 
+// plain copy, 16 bytes per lane, grid-stride: the yardstick for HBM counters and for the
+// achievable copy bandwidth of the box
+__global__ void copy_16B(const uint4 *__restrict__ src, uint4 *__restrict__ dst, uint64_t n16)
+{
+    uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride)
+        dst[i] = src[i];
+}
+
 }  // namespace
+
+// Copies `bytes` (a multiple of 16) from src to dst, both device pointers.
+extern "C" int moe_inputs_copy(void *dst, const void *src, uint64_t bytes, void *stream)
+{
+    if (bytes == 0 || bytes % 16 != 0)
+        return bytes == 0 ? 0 : -1;
+    hipLaunchKernelGGL(copy_16B, dim3(256 * 32), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), bytes / 16);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
 
 // out: device pointer to `count` elements (fp32, or bf16 when bf16 != 0) that receive
 // flat elements [start, start+count) of the stream identified by `key`.

@@ -5,7 +5,8 @@ import ctypes
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(HERE, "libmoe_hub.so")
+# MOE_HUB_LIBRARY selects another build of the same library (A/B timing of two builds)
+_LIB_PATH = os.environ.get("MOE_HUB_LIBRARY") or os.path.join(HERE, "libmoe_hub.so")
 
 BF16, F32 = 0, 1
 SCORE_SOFTMAX_TOPK, SCORE_SIGMOID_TOPK = 0, 1

@@ -16,8 +16,6 @@
 // together share weight tiles; workgroup ids are spread so that each XCD's L2
 // sees a compact patch of that order.  Nothing about the routing result is read
 // on the host.
-#include <stdlib.h>
-
 #include "common.h"
 #include "grouped_gemm.h"
 
@@ -249,6 +247,9 @@ int check_ffn_shape(int dtype, int64_t H, int64_t F)
     return MOE_OK;
 }
 
+// consecutive tiles each XCD takes at a time (see tile_of_workgroup)
+constexpr int kPatch = 16;
+
 struct FfnWorkspace {
     uint16_t *a;
     TileTableHeader *hdr1, *hdr2;
@@ -302,17 +303,7 @@ int launch_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t 
     const FfnWorkspace k = carve(p, ws);
     const uint16_t *xpb = static_cast<const uint16_t *>(xp);
     const uint16_t *wg = static_cast<const uint16_t *>(W_gate), *wu = static_cast<const uint16_t *>(W_up);
-    static const int variant = getenv("MOE_GEMM_VARIANT") ? atoi(getenv("MOE_GEMM_VARIANT")) : 0;
-    static const int kPatch = getenv("MOE_GEMM_PATCH") ? atoi(getenv("MOE_GEMM_PATCH")) : 32;
-    if (p.big && variant == 1)
-        launch_gemm<256, 256, 2, 4, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
-    else if (p.big && variant == 2)
-        launch_gemm<256, 256, 2, 2, true, 64, 2>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
-    else if (p.big && variant == 3)
-        launch_gemm<256, 256, 2, 2, true, 32, 2>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
-    else if (p.big && variant == 4)
-        launch_gemm<256, 256, 2, 2, true, 32, 3>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
-    else if (p.big)
+    if (p.big)
         launch_gemm<256, 256, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
     else
         launch_gemm<128, 128, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
@@ -332,17 +323,7 @@ int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     const FfnWorkspace k = carve(p, ws);
     const uint16_t *wd = static_cast<const uint16_t *>(W_down);
     uint16_t *yb = static_cast<uint16_t *>(y);
-    static const int variant = getenv("MOE_GEMM_VARIANT") ? atoi(getenv("MOE_GEMM_VARIANT")) : 0;
-    static const int kPatch = getenv("MOE_GEMM_PATCH") ? atoi(getenv("MOE_GEMM_PATCH")) : 32;
-    if (p.big && variant == 1)
-        launch_gemm<256, 256, 2, 4, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
-    else if (p.big && variant == 2)
-        launch_gemm<256, 256, 2, 2, false, 64, 2>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
-    else if (p.big && variant == 3)
-        launch_gemm<256, 256, 2, 2, false, 32, 2>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
-    else if (p.big && variant == 4)
-        launch_gemm<256, 256, 2, 2, false, 32, 3>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
-    else if (p.big)
+    if (p.big)
         launch_gemm<256, 256, 2, 2, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
     else
         launch_gemm<128, 128, 2, 2, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);

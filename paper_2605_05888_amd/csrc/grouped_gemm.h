@@ -152,7 +152,7 @@ struct GemmCfg {
 };
 
 template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK, int kStages>
-__global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
+__global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void grouped_gemm_bf16(
     const uint16_t *__restrict__ A, int64_t M, int Kdim, int Ndim,
     const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
     uint16_t *__restrict__ C, const TileTableHeader *__restrict__ hdr,
@@ -176,23 +176,26 @@ __global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
     //      in one 32-bit register (row offset inside the tile, fixed for the whole K loop); the tile
     //      base sits in the scalar resource and the K offset in a scalar register.
     const int ld_row = lane / kChunks, ld_pc = lane % kChunks;
+    //      Rows past the end of the segment (and columns past Ndim) lie beyond the resource's byte
+    //      count: the bounds check returns zeros for them without touching memory.
     const int64_t rows_left = (int64_t)te.m_end - te.m0; // >= 1
+    const int64_t a_bytes = (rows_left < BM ? rows_left : BM) * (int64_t)Kdim * 2;
     const __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t *>(A + (int64_t)te.m0 * Kdim), 0, 0xFFFFFFFFu, 0x00020000);
+        const_cast<uint16_t *>(A + (int64_t)te.m0 * Kdim), 0, (unsigned)a_bytes, 0x00020000);
     int a_off[Cfg::kAGroups];
 #pragma unroll
     for (int g = 0; g < Cfg::kAGroups; ++g) {
         const int r = (wave * Cfg::kAGroups + g) * Cfg::kGroupRows + ld_row;
-        const int rr = r < rows_left ? r : (int)rows_left - 1; // rows past the segment repeat its last row; never stored
-        a_off[g] = (rr * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8)) * 2;
+        a_off[g] = (r * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8)) * 2;
     }
     // B rows of one wavefront (kSwiglu): first half gate columns, second half the same up columns.
     // A load group never straddles the two halves, so its resource is wave-uniform.
     const int cols_left = Ndim - n0; // >= 1
+    const int64_t b_bytes = (cols_left < Cfg::kOutCols ? cols_left : Cfg::kOutCols) * (int64_t)Kdim * 2;
     const __amdgpu_buffer_rsrc_t rs_b0 = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t *>(B0 + ((int64_t)te.expert * Ndim + n0) * Kdim), 0, 0xFFFFFFFFu, 0x00020000);
+        const_cast<uint16_t *>(B0 + ((int64_t)te.expert * Ndim + n0) * Kdim), 0, (unsigned)b_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_b1 = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t *>((kSwiglu ? B1 : B0) + ((int64_t)te.expert * Ndim + n0) * Kdim), 0, 0xFFFFFFFFu,
+        const_cast<uint16_t *>((kSwiglu ? B1 : B0) + ((int64_t)te.expert * Ndim + n0) * Kdim), 0, (unsigned)b_bytes,
         0x00020000);
     int b_off[Cfg::kBGroups];
 #pragma unroll
@@ -205,8 +208,6 @@ __global__ __launch_bounds__(WM *WN *kWave) void grouped_gemm_bf16(
         } else {
             col = r;
         }
-        if (col >= cols_left)
-            col = cols_left - 1;
         b_off[g] = (col * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8)) * 2;
     }
     const int KT = Kdim / kBK;
