@@ -304,7 +304,7 @@ int launch_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t 
     const uint16_t *xpb = static_cast<const uint16_t *>(xp);
     const uint16_t *wg = static_cast<const uint16_t *>(W_gate), *wu = static_cast<const uint16_t *>(W_up);
     if (p.big)
-        launch_gemm<256, 256, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
+        launch_gemm<256, 256, 2, 2, true, 64, 2>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
     else
         launch_gemm<128, 128, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
     return check_launch("moe_ffn_gate_up");
@@ -324,7 +324,7 @@ int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     const uint16_t *wd = static_cast<const uint16_t *>(W_down);
     uint16_t *yb = static_cast<uint16_t *>(y);
     if (p.big)
-        launch_gemm<256, 256, 2, 2, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
+        launch_gemm<256, 256, 2, 2, false, 64, 2>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
     else
         launch_gemm<128, 128, 2, 2, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
     return check_launch("moe_ffn_down");
