@@ -162,6 +162,17 @@ def cpu_baseline(cfg, layer, target_seconds):
                       f"over all {E_run} experts at full H and F, combine); {t:.1f} s of CPU time"}
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch from the committed rocprofv3 counter summaries (profiles/*_hbm_traffic.md), or None."""
+    import glob
+    for path in glob.glob(os.path.join(ROOT, "profiles", "*_hbm_traffic.md")):
+        for line in open(path):
+            t = line.split()
+            if len(t) == 4 and t[0] == "traffic_bytes" and t[1] == workload and t[2] == kernel:
+                return float(t[3])
+    return None
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -210,7 +221,8 @@ def main():
                    "F": F, "G": G, "routed_rows": R, "activation_buffer_sets": nbuf},
         "roofline": {"kernel": "grouped_gemm_bf16 (gate/up projection with fused SwiGLU)", "bound": "mfma",
                      "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
-                     "flops_per_launch": flops_gu, "avg_launch_us": us["ffn_gate_up"], "traffic": None},
+                     "flops_per_launch": flops_gu, "avg_launch_us": us["ffn_gate_up"],
+                     "traffic": measured_traffic(args.workload, "ffn_gate_up")},
         "ffn": {"tflops_gate_up": ach, "tflops_down": flops_dn / t_dn / 1e12,
                 "tflops_both": (flops_gu + flops_dn) / (t_gu + t_dn) / 1e12,
                 "mfma_frac_both": (flops_gu + flops_dn) / (t_gu + t_dn) / 1e12 / PEAK_BF16_TFLOPS},
