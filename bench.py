@@ -33,6 +33,8 @@ WORKLOAD_TEXT = {
     "gptoss": "gpt-oss-shaped layer, Zipf(1.0) expert popularity",
     "dsv3": "DeepSeek-V3-shaped routed layer",
     "dsv3_ep": "one expert-parallel rank's share of a DeepSeek-V3-shaped layer (32 destinations, 8 local experts)",
+    "qwen2moe": "Qwen2-MoE-2.7B-shaped layer (paper Table II)",
+    "phi35moe": "Phi-3.5-MoE-shaped layer (paper Table II)",
 }
 
 
@@ -42,6 +44,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="mixtral", choices=list(WORKLOAD_TEXT))
+    ap.add_argument("--tokens", type=int, default=0, help="override the workload's token count (token-count sweeps)")
     ap.add_argument("--nbuf", type=int, default=0, help="activation buffer sets rotated per step (0 = auto)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample (0 = skip)")
     return ap.parse_args()
@@ -185,6 +188,9 @@ def main():
     import paper_2605_05888_amd as hub
     hub.load_library(build_if_missing=False)     # fail loudly if the HIP library is not built
     cfg = mi.CONFIGS[args.workload]
+    if args.tokens > 0:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, N=args.tokens)
     N, H, E, K, F, G = cfg.N, cfg.H, cfg.E, cfg.K, cfg.F, cfg.G
     R, b = N * K, cfg.elt_bytes
     act_bytes = (2 * N * H + 2 * R * H + R * F) * b

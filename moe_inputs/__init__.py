@@ -77,6 +77,9 @@ CONFIGS = {
     "gptoss": MoEConfig("gptoss", 8192, 2880, 128, 4, 2880, 1, BF16, SCORE_SOFTMAX_TOPK, 1.0, 2),
     "dsv3": MoEConfig("dsv3", 16384, 7168, 256, 8, 2048, 1, BF16, SCORE_SIGMOID_TOPK, 0.0, 3),
     "dsv3_ep": MoEConfig("dsv3_ep", 8192, 7168, 256, 8, 2048, 32, BF16, SCORE_SIGMOID_TOPK, 1.2, 4),
+    # the two other model shapes of the paper's Table II (Mixtral 8x7B is "mixtral" above)
+    "qwen2moe": MoEConfig("qwen2moe", 8192, 2048, 64, 4, 1408, 1, BF16, SCORE_SOFTMAX_TOPK, 0.0, 5),
+    "phi35moe": MoEConfig("phi35moe", 8192, 4096, 16, 2, 6400, 1, BF16, SCORE_SOFTMAX_TOPK, 0.0, 6),
 }
 
 

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 import moe_inputs as mi  # noqa: E402
 import oracle  # noqa: E402
 
-FULL = ["mixtral", "gptoss", "dsv3", "dsv3_ep"]
+FULL = ["mixtral", "gptoss", "dsv3", "dsv3_ep", "qwen2moe", "phi35moe"]
 _state = {}
 
 

@@ -269,3 +269,21 @@ def test_error_returns_launch_nothing(G):
                               torch.zeros((1, 64, 64), dtype=torch.bfloat16, device="cuda:0"),
                               torch.zeros((1, 64, 64), dtype=torch.bfloat16, device="cuda:0"),
                               torch.zeros_like(xp), None)       # missing workspace
+
+
+def test_repeated_calls_are_bit_identical(G):
+    """No atomics and no order dependence anywhere on the path: two runs give the same bits."""
+    import moe_inputs.device as mid
+    cfg = SMALL["gptoss"]
+    x, Wr = mi.host_tensor(cfg, mi.STREAM_X), mi.host_tensor(cfg, mi.STREAM_W_ROUTER)
+    Wg, Wu, Wd = (mid.to_device(mi.host_tensor(cfg, s)) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    dx, dWr, db = mid.to_device(x), mid.to_device(Wr), mid.to_device(mi.router_bias(cfg))
+    runs = []
+    for _ in range(3):
+        idx, w, lg = G.gpu_route(dx, dWr, db, cfg.K, cfg.score_mode)
+        lay = G.gpu_layout(idx, cfg.E, cfg.G)
+        xp = G.gpu_permute(dx, cfg.K, lay)
+        y = G.gpu_ffn(xp, lay["expert_offsets"], Wg, Wu, Wd)
+        out = G.gpu_combine(y, cfg.K, lay["slot_of_row"], w)
+        runs.append([G.host(t).tobytes() for t in (idx, w, lg, lay["slot_of_row"], lay["row_of_slot"], xp, y, out)])
+    assert runs[0] == runs[1] == runs[2]
