@@ -7,8 +7,8 @@
 // Both operands of both GEMMs have the reduction index contiguous, so every lane
 // fetches its matrix-core operand (8 consecutive bf16 of one row) with a single
 // 16-byte LDS read.  bf16 path: v_mfma_f32_32x32x16_bf16, fp32 accumulators,
-// LDS tiles double buffered with a 16-byte-chunk XOR swizzle, one barrier per
-// K tile.  GEMM1 keeps gate and up columns of the same f in one wavefront, so
+// operand tiles brought global -> LDS without staging registers into a ring of
+// XOR-swizzled units (grouped_gemm.h), one barrier per K tile.  GEMM1 keeps gate and up columns of the same f in one wavefront, so
 // the activation is applied to the accumulators and `g`, `u` never reach memory.
 //
 // Scheduling is device side: a small kernel turns seg_offsets into a tile table
@@ -218,13 +218,20 @@ size_t ffn_workspace_bytes(int64_t M, int64_t H, int64_t F, int E_local, int dty
     return make_plan(M, H, F, E_local).total;
 }
 
-template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK = 32, int kStages = 4>
+// 256x256x64 tile: ring of 5 units (all 160 KiB of LDS); per window the 8 B loads of a wavefront go
+// out under the first two k-steps after the barrier, the 8 A loads under the other two.
+#ifndef MOE_UNITS64
+#define MOE_UNITS64 5
+#define MOE_DISTA64 0x0044
+#define MOE_DISTB64 0x4400
+#endif
+template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK, int kUnits, int kDistA, int kDistB>
 static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const uint16_t *B0,
                         const uint16_t *B1, uint16_t *C, const TileTableHeader *hdr,
                         const TileEntry *table, int max_tiles, int patch, hipStream_t st)
 {
-    using Cfg = GemmCfg<BM, BN, WM, WN, kSwiglu, kBK, kStages>;
-    auto kern = grouped_gemm_bf16<BM, BN, WM, WN, kSwiglu, kBK, kStages>;
+    using Cfg = GemmCfg<BM, BN, WM, WN, kSwiglu, kBK, kUnits>;
+    auto kern = grouped_gemm_bf16<BM, BN, WM, WN, kSwiglu, kBK, kUnits, kDistA, kDistB>;
     static bool attr_set = false; // raising the dynamic LDS limit is idempotent
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -304,9 +311,9 @@ int launch_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t 
     const uint16_t *xpb = static_cast<const uint16_t *>(xp);
     const uint16_t *wg = static_cast<const uint16_t *>(W_gate), *wu = static_cast<const uint16_t *>(W_up);
     if (p.big)
-        launch_gemm<256, 256, 2, 2, true, 64, 2>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
+        launch_gemm<256, 256, 2, 2, true, 64, MOE_UNITS64, MOE_DISTA64, MOE_DISTB64>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
     else
-        launch_gemm<128, 128, 2, 2, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
+        launch_gemm<128, 128, 2, 2, true, 32, 8, 0x20, 0x02>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
     return check_launch("moe_ffn_gate_up");
 }
 
@@ -324,9 +331,9 @@ int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     const uint16_t *wd = static_cast<const uint16_t *>(W_down);
     uint16_t *yb = static_cast<uint16_t *>(y);
     if (p.big)
-        launch_gemm<256, 256, 2, 2, false, 64, 2>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
+        launch_gemm<256, 256, 2, 2, false, 64, MOE_UNITS64, MOE_DISTA64, MOE_DISTB64>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
     else
-        launch_gemm<128, 128, 2, 2, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
+        launch_gemm<128, 128, 2, 2, false, 32, 8, 0x20, 0x02>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
     return check_launch("moe_ffn_down");
 }
 

@@ -5,8 +5,9 @@
 // BM x BN tile; every wavefront owns a (BM/WM) x (BN/WN) sub-tile as 32x32 blocks of
 // v_mfma_f32_32x32x16_bf16.
 //
-// Pipeline (K tiles of BK = 32 or 64 elements, S LDS stages of (BM+BN) x BK bf16):
-//   * global -> LDS goes through global_load_lds_dwordx4: no staging registers, no
+// Pipeline (K tiles of BK = 32 or 64 elements; LDS is a ring of U units, a unit holding the A rows
+// or the B rows of one K tile):
+//   * global -> LDS goes through buffer_load_dwordx4 ... lds: no staging registers, no
 //     ds_write.  A wavefront instruction fills 1 KiB of consecutive tile rows; the
 //     16-byte chunk a lane fetches is chosen so that the LDS image is XOR swizzled
 //     and the 16-byte operand reads are bank-conflict free.
@@ -14,10 +15,13 @@
 //     operands of k-step ks+1 are read from LDS while the MFMAs of ks run.  Before
 //     the last k-step of tile kt there is ONE barrier: by then every wavefront has
 //     read all of tile kt, and tile kt+1 has landed (own loads: vmcnt, everyone's:
-//     the barrier).  After it the loads of tile kt+S go into the stage tile kt just
-//     left and the first operands of tile kt+1 are read, both under the MFMAs of
-//     the last k-step.  So S tiles are in flight or in use at any time and neither
-//     LDS latency nor the global prefetch is exposed.
+//     the barrier).  The barrier frees the two units of tile kt.
+//   * loads are issued a few at a time under the MFMAs of every k-step, the B rows of
+//     tile kt+U/2 into a unit just freed.  With an odd U (5 units of 32 KiB for the
+//     256x256x64 tile: all 160 KiB) one unit is spare, so the A rows run one tile further
+//     ahead than the B rows and the B loads can all go out right after the barrier: every
+//     load then has two k-steps or more (about a microsecond) to land before the barrier
+//     that waits for it, which is what a load from HBM needs here.
 //   * The matrix-core operands are swapped (weights as the "A" operand), so a lane
 //     ends up with 4 consecutive output columns of one row per accumulator
 //     quadruple and stores them as one 8-byte vector.
@@ -122,7 +126,33 @@ __device__ __forceinline__ void interleave_under_mfma()
         __builtin_amdgcn_sched_group_barrier(0x008, kRest, 0);
 }
 
-template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK, int kStages>
+// Loads of position p of a window, from a hexadecimal digit string (most significant digit =
+// position 0).
+constexpr int part_loads(int dist, int parts, int p) { return (dist >> (4 * (parts - 1 - p))) & 15; }
+constexpr int part_first(int dist, int parts, int p)
+{
+    int s = 0;
+    for (int i = 0; i < p; ++i)
+        s += part_loads(dist, parts, i);
+    return s;
+}
+// Loads of a window that are issued after the last load the next barrier has to wait for.  Inside a
+// position the B loads go first, then the A loads; `a_needed` says whether the A loads of the window
+// belong to the same K tile as its B loads (else they belong to a later one and nobody waits yet).
+constexpr int window_tail(int dist_a, int dist_b, int parts, bool a_needed)
+{
+    int after = 0;
+    for (int p = parts - 1; p >= 0; --p) {
+        if (a_needed && part_loads(dist_a, parts, p) > 0)
+            return after;
+        after += part_loads(dist_a, parts, p);
+        if (part_loads(dist_b, parts, p) > 0)
+            return after;
+    }
+    return after;
+}
+
+template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK, int kUnits>
 struct GemmCfg {
     static constexpr int kWaves = WM * WN;
     static constexpr int kThreads = kWaves * kWave;
@@ -137,21 +167,21 @@ struct GemmCfg {
     static constexpr int kBGroups = BN / kGroupRows / kWaves;
     static constexpr int kLoadsPerTile = kAGroups + kBGroups; // per lane, per K tile
     static constexpr int kKSteps = kBK / 16;
-    static constexpr int kMfmaPerStep = kBlkM * kBlkN;
-    static constexpr int kReadsPerStep = kBlkM + kBlkN;
     static constexpr int kOutCols = kSwiglu ? BN / 2 : BN;
-    static constexpr int kATileBytes = BM * kRowBytes;
-    static constexpr int kStageBytes = (BM + BN) * kRowBytes;
-    static constexpr size_t kLdsBytes = (size_t)kStages * kStageBytes;
+    // LDS is a ring of kUnits units; a unit holds the A rows or the B rows of one K tile.
+    static constexpr int kUnitBytes = (BM > BN ? BM : BN) * kRowBytes;
+    static constexpr int kDepth = kUnits / 2;  // K tiles whose B part fits besides the one in use
+    static constexpr int kAheadA = kUnits % 2; // an odd ring lets the A loads run one tile further ahead
+    static constexpr size_t kLdsBytes = (size_t)kUnits * kUnitBytes;
     static_assert(kBK == 32 || kBK == 64, "K tile");
-    static_assert(kStages >= 2, "stages");
+    static_assert(kUnits >= 4, "two K tiles at least");
     static_assert(kWaveM % 32 == 0 && kWaveN % 32 == 0, "wave tile must be 32x32 blocks");
     static_assert(BM % (kGroupRows * kWaves) == 0 && BN % (kGroupRows * kWaves) == 0, "load groups");
     static_assert(!kSwiglu || kBlkN % 2 == 0, "gate and up halves");
-    static_assert(kLoadsPerTile * (kStages - 1) <= 63, "vmcnt budget");
+    static_assert(kLoadsPerTile * (kDepth + kAheadA) <= 63, "vmcnt budget");
 };
 
-template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK, int kStages>
+template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK, int kUnits, int kDistA, int kDistB>
 __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void grouped_gemm_bf16(
     const uint16_t *__restrict__ A, int64_t M, int Kdim, int Ndim,
     const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
@@ -159,8 +189,9 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
     const TileEntry *__restrict__ table, int patch)
 {
 #if defined(__HIP_DEVICE_COMPILE__) // the body uses device-only types (buffer resources); the host pass only needs the stub
-    using Cfg = GemmCfg<BM, BN, WM, WN, kSwiglu, kBK, kStages>;
+    using Cfg = GemmCfg<BM, BN, WM, WN, kSwiglu, kBK, kUnits>;
     constexpr int kChunks = Cfg::kChunks, kRowBytes = Cfg::kRowBytes, kKSteps = Cfg::kKSteps;
+    constexpr int kDepth = Cfg::kDepth, kAheadA = Cfg::kAheadA;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int L = tile_of_workgroup(blockIdx.x, patch);
     if (L >= hdr->num_tiles)
@@ -180,8 +211,7 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
     //      count: the bounds check returns zeros for them without touching memory.
     const int64_t rows_left = (int64_t)te.m_end - te.m0; // >= 1
     const int64_t a_bytes = (rows_left < BM ? rows_left : BM) * (int64_t)Kdim * 2;
-    const __amdgpu_buffer_rsrc_t rs_a = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t *>(A + (int64_t)te.m0 * Kdim), 0, (unsigned)a_bytes, 0x00020000);
+    const uint16_t *a_base = A + (int64_t)te.m0 * Kdim;
     int a_off[Cfg::kAGroups];
 #pragma unroll
     for (int g = 0; g < Cfg::kAGroups; ++g) {
@@ -192,11 +222,8 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
     // A load group never straddles the two halves, so its resource is wave-uniform.
     const int cols_left = Ndim - n0; // >= 1
     const int64_t b_bytes = (cols_left < Cfg::kOutCols ? cols_left : Cfg::kOutCols) * (int64_t)Kdim * 2;
-    const __amdgpu_buffer_rsrc_t rs_b0 = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t *>(B0 + ((int64_t)te.expert * Ndim + n0) * Kdim), 0, (unsigned)b_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rs_b1 = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t *>((kSwiglu ? B1 : B0) + ((int64_t)te.expert * Ndim + n0) * Kdim), 0, (unsigned)b_bytes,
-        0x00020000);
+    const uint16_t *b0_base = B0 + ((int64_t)te.expert * Ndim + n0) * Kdim;
+    const uint16_t *b1_base = (kSwiglu ? B1 : B0) + ((int64_t)te.expert * Ndim + n0) * Kdim;
     int b_off[Cfg::kBGroups];
 #pragma unroll
     for (int g = 0; g < Cfg::kBGroups; ++g) {
@@ -211,55 +238,58 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
         b_off[g] = (col * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8)) * 2;
     }
     const int KT = Kdim / kBK;
+    // A K tile past the end of the reduction is "loaded" through a resource of zero bytes: every
+    // lane is out of range, nothing is fetched and zeros land in a unit nobody reads.  So the
+    // loop issues the same number of loads in every iteration and the vmcnt arithmetic below
+    // holds from the first tile to the last.
+    auto resource = [&](const uint16_t *base, int64_t bytes, int tile) {
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base), 0,
+                                                 tile < KT ? (unsigned)bytes : 0u, 0x00020000);
+    };
+    using lds_ptr = __attribute__((address_space(3))) void *;
+    auto load_a_group = [&](int tile, int unit, int g) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            resource(a_base, a_bytes, tile),
+            (lds_ptr)(lds + unit * Cfg::kUnitBytes + (wave * Cfg::kAGroups + g) * 1024), 16, a_off[g],
+            tile * (kBK * 2), 0, 0);
+    };
+    auto load_b_group = [&](int tile, int unit, int g) {
+        const int r0 = (wave * Cfg::kBGroups + g) * Cfg::kGroupRows; // uniform
+        const bool up = kSwiglu && (r0 % Cfg::kWaveN) >= Cfg::kWaveN / 2;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            resource(up ? b1_base : b0_base, b_bytes, tile),
+            (lds_ptr)(lds + unit * Cfg::kUnitBytes + (wave * Cfg::kBGroups + g) * 1024), 16, b_off[g],
+            tile * (kBK * 2), 0, 0);
+    };
 
-    // The kLoadsPerTile loads of a tile (A groups, then B groups) are issued in kKSteps parts, one
-    // part under each k-step's MFMAs, so that the four wavefronts never push a whole tile into
-    // the memory pipeline in one burst right after the barrier.
-    constexpr int kPartLoads = Cfg::kLoadsPerTile / kKSteps;
-    static_assert(Cfg::kLoadsPerTile % kKSteps == 0, "loads per part");
-    auto issue_part = [&](int kt, auto part_tag) {
-        constexpr int part = decltype(part_tag)::value;
-        unsigned char *stage = lds + (kt % kStages) * Cfg::kStageBytes;
-        const int koff = kt * (kBK * 2);
+    // ---- the ring.  K tile t keeps its A rows in unit (2t) % kUnits and its B rows in unit
+    //      (2t+1) % kUnits.  `u` below is always the A unit of the tile being multiplied.
+    auto wrap = [](int x) { return x >= kUnits ? x - kUnits : x; };
+    auto unit_a = [&](int u, int ahead) { return wrap(u + (2 * ahead) % kUnits); };
+    auto unit_b = [&](int u, int ahead) { return wrap(u + (2 * ahead + 1) % kUnits); };
+
+    // ---- load schedule.  The barrier that ends the reads of tile t opens a "window": the units of
+    //      tile t are free, and until the next barrier the loads of B(t + kDepth) and of
+    //      A(t + kDepth + kAheadA) are issued, in kKSteps positions: position 0 under the last
+    //      k-step of tile t, position p under k-step p-1 of tile t+1 (kDistB / kDistA say how many
+    //      loads each position takes; B first, then A).  Spreading them keeps the four wavefronts
+    //      from pushing a whole tile into the memory pipeline in one burst; putting the B loads
+    //      early gives them two to three k-steps to land before the barrier that needs them, and
+    //      the A loads, which are needed one tile later when the ring is odd, fill the rest.
+    static_assert(part_first(kDistA, kKSteps, kKSteps) == Cfg::kAGroups, "A loads of a window");
+    static_assert(part_first(kDistB, kKSteps, kKSteps) == Cfg::kBGroups, "B loads of a window");
+    auto issue_position = [&](int t, int u, auto pos_tag) { // window opened by the barrier of tile t
+        constexpr int p = decltype(pos_tag)::value;
 #pragma unroll
-        for (int q = part * kPartLoads; q < (part + 1) * kPartLoads; ++q) {
-            if (q < Cfg::kAGroups) {
-                const int g = q;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    rs_a, (__attribute__((address_space(3))) void *)(stage + (wave * Cfg::kAGroups + g) * 1024), 16,
-                    a_off[g], koff, 0, 0);
-            } else {
-                const int g = q - Cfg::kAGroups;
-                const int r0 = (wave * Cfg::kBGroups + g) * Cfg::kGroupRows; // uniform
-                const bool up = kSwiglu && (r0 % Cfg::kWaveN) >= Cfg::kWaveN / 2;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                    up ? rs_b1 : rs_b0,
-                    (__attribute__((address_space(3))) void *)(stage + Cfg::kATileBytes +
-                                                               (wave * Cfg::kBGroups + g) * 1024),
-                    16, b_off[g], koff, 0, 0);
-            }
-        }
+        for (int g = part_first(kDistB, kKSteps, p); g < part_first(kDistB, kKSteps, p + 1); ++g)
+            load_b_group(t + kDepth, unit_b(u, kDepth), g);
+#pragma unroll
+        for (int g = part_first(kDistA, kKSteps, p); g < part_first(kDistA, kKSteps, p + 1); ++g)
+            load_a_group(t + kDepth + kAheadA, unit_a(u, kDepth + kAheadA), g);
     };
-    auto issue_tile = [&](int kt) {
-        issue_part(kt, std::integral_constant<int, 0>{});
-        if constexpr (kKSteps > 1)
-            issue_part(kt, std::integral_constant<int, 1>{});
-        if constexpr (kKSteps > 2) {
-            issue_part(kt, std::integral_constant<int, 2>{});
-            issue_part(kt, std::integral_constant<int, 3>{});
-        }
-    };
-    // part ks+1 of a tile goes under k-step ks
-    auto issue_part_for_step = [&](int kt, int ks) {
-        if (ks == 0)
-            issue_part(kt, std::integral_constant<int, 1>{});
-        if constexpr (kKSteps > 2) {
-            if (ks == 1)
-                issue_part(kt, std::integral_constant<int, 2>{});
-            if (ks == 2)
-                issue_part(kt, std::integral_constant<int, 3>{});
-        }
-    };
+    auto loads_at = [](int p) { return part_loads(kDistA, kKSteps, p) + part_loads(kDistB, kKSteps, p); };
+    // loads that may still be in flight when a barrier needs the next tile complete
+    constexpr int kInFlight = (kDepth - 2) * Cfg::kLoadsPerTile + window_tail(kDistA, kDistB, kKSteps, kAheadA == 0);
 
     // ---- operand reads: lane (i = lane%32, kg = lane/32) reads chunk (2*ks + kg) of row i of a block.
     //      Block and wavefront offsets are multiples of 32 rows, so the key depends on i only, and
@@ -267,16 +297,15 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
     const int fr = lane % 32, kg = lane / 32;
     const int key = row_key<kChunks>(fr);
     const int a_off0 = (wm * Cfg::kWaveM + fr) * kRowBytes + ((kg ^ key) << 4);
-    const int b_off0 = Cfg::kATileBytes + (wn * Cfg::kWaveN + fr) * kRowBytes + ((kg ^ key) << 4);
+    const int b_off0 = (wn * Cfg::kWaveN + fr) * kRowBytes + ((kg ^ key) << 4);
 
     bf16x8 fa[2][Cfg::kBlkM], fb[2][Cfg::kBlkN];
     // `act` = number of this wavefront's 32-row blocks that hold rows of the segment: blocks past
     // the end of a ragged segment are neither read nor multiplied.
-    auto read_frags = [&](int kt, int ks, int slot, auto act_tag) {
+    auto read_frags = [&](int u, int ks, int slot, auto act_tag) { // u = A unit of the tile
         constexpr int kAct = decltype(act_tag)::value;
-        const unsigned char *stage = lds + (kt % kStages) * Cfg::kStageBytes;
-        const unsigned char *pa = stage + (a_off0 ^ (ks << 5));
-        const unsigned char *pb = stage + (b_off0 ^ (ks << 5));
+        const unsigned char *pa = lds + u * Cfg::kUnitBytes + (a_off0 ^ (ks << 5));
+        const unsigned char *pb = lds + wrap(u + 1) * Cfg::kUnitBytes + (b_off0 ^ (ks << 5));
 #pragma unroll
         for (int i = 0; i < kAct; ++i)
             fa[slot][i] = *reinterpret_cast<const bf16x8 *>(pa + i * 32 * kRowBytes);
@@ -307,55 +336,55 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
 
     auto pipeline = [&](auto act) {
         constexpr int kAct = decltype(act)::value;
-        // ---- prologue: tiles 0 .. kStages-2 and the first part of tile kStages-1 in flight, tile 0 landed
-    #pragma unroll
-        for (int t = 0; t + 1 < kStages; ++t)
-            if (t < KT)
-                issue_tile(t);
-        if (kStages - 1 < KT)
-            issue_part(kStages - 1, std::integral_constant<int, 0>{});
-        if (KT >= kStages)
-            MOE_WAIT_VMCNT((kStages - 2) * Cfg::kLoadsPerTile + kPartLoads);
-        else
-            wait_tiles_in_flight<Cfg::kLoadsPerTile, kStages - 2>(KT - 1); // all but tile 0
+        constexpr int kMfma = kAct * Cfg::kBlkN, kReads = kAct ? kAct + Cfg::kBlkN : 0;
+        // ---- prologue: everything the windows before tile 0 would have issued, then position 0
+        //      of the window before tile 0; tile 0 landed
+#pragma unroll
+        for (int t = 0; t + 1 < kDepth + kAheadA; ++t) {
+#pragma unroll
+            for (int g = 0; g < Cfg::kAGroups; ++g)
+                load_a_group(t, (2 * t) % kUnits, g);
+            if (t + 1 < kDepth) {
+#pragma unroll
+                for (int g = 0; g < Cfg::kBGroups; ++g)
+                    load_b_group(t, (2 * t + 1) % kUnits, g);
+            }
+        }
+        issue_position(-1, kUnits - 2, std::integral_constant<int, 0>{});
+        // in flight after B(0): tiles 1 .. kDepth-2, the A rows that run ahead, position 0
+        MOE_WAIT_VMCNT((kDepth - 2) * Cfg::kLoadsPerTile + kAheadA * Cfg::kAGroups + loads_at(0));
         lds_barrier();
         read_frags(0, 0, 0, act);
 
-        // steady state: every step exists, so the body is branch free (a branch around the LDS
-        // reads would make the compiler wait for them before MFMAs that do not need them)
-        int kt = 0;
-        for (; kt + kStages < KT; ++kt) {
-    #pragma unroll
-            for (int ks = 0; ks + 1 < kKSteps; ++ks) {
-                issue_part_for_step(kt + kStages - 1, ks); // rest of the tile begun one iteration ago
-                read_frags(kt, ks + 1, (ks + 1) & 1, act);
-                mfma_all(ks & 1, act);
-                interleave_under_mfma<kAct * Cfg::kBlkN, (kAct ? kAct + Cfg::kBlkN : 0), kPartLoads>();
+        // k-step ks of tile kt (not its last): position ks+1 of the window goes out, the operands
+        // of k-step ks+1 are read, all under this step's MFMAs
+        auto kstep = [&](int kt, int u, auto ks_tag) {
+            constexpr int ks = decltype(ks_tag)::value;
+            issue_position(kt - 1, wrap(u + kUnits - 2), std::integral_constant<int, ks + 1>{});
+            read_frags(u, ks + 1, (ks + 1) & 1, act);
+            mfma_all(ks & 1, act);
+            interleave_under_mfma<kMfma, kReads, loads_at(ks + 1)>();
+        };
+        // The body is branch free (a branch around the LDS reads would make the compiler wait for
+        // them before MFMAs that do not need them).
+        int u = 0;
+        for (int kt = 0; kt < KT; ++kt) {
+            kstep(kt, u, std::integral_constant<int, 0>{});
+            if constexpr (kKSteps > 2) {
+                kstep(kt, u, std::integral_constant<int, 1>{});
+                kstep(kt, u, std::integral_constant<int, 2>{});
             }
-            __builtin_amdgcn_sched_barrier(0);                   // keep this k-step's MFMAs above the waits
-            MOE_WAIT_LGKM0();                                    // my reads of tile kt are complete
-            MOE_WAIT_VMCNT((kStages - 2) * Cfg::kLoadsPerTile);  // my part of tile kt+1 has landed
-            lds_barrier();                                       // ... and everyone's
-            issue_part(kt + kStages, std::integral_constant<int, 0>{}); // into the stage tile kt just left
-            read_frags(kt + 1, 0, 0, act);
+            __builtin_amdgcn_sched_barrier(0); // keep this k-step's MFMAs above the waits
+            MOE_WAIT_LGKM0();                  // my reads of tile kt are complete
+            MOE_WAIT_VMCNT(kInFlight);         // my part of tile kt+1 has landed
+            lds_barrier();                     // ... and everyone's; the units of tile kt are free
+            issue_position(kt, u, std::integral_constant<int, 0>{});
+            read_frags(unit_a(u, 1), 0, 0, act); // after the last tile: a unit of zeros, unused
             mfma_all((kKSteps - 1) & 1, act);
-            interleave_under_mfma<kAct * Cfg::kBlkN, (kAct ? kAct + Cfg::kBlkN : 0), kPartLoads>();
+            interleave_under_mfma<kMfma, kReads, loads_at(0)>();
+            u = unit_a(u, 1);
         }
-        // last kStages tiles: only the rest of the last tile is still to be issued
-        for (; kt < KT; ++kt) {
-            const bool rest = kt + kStages - 1 < KT; // true once, for the first of these iterations
-    #pragma unroll
-            for (int ks = 0; ks + 1 < kKSteps; ++ks) {
-                if (rest)
-                    issue_part_for_step(kt + kStages - 1, ks);
-                read_frags(kt, ks + 1, (ks + 1) & 1, act);
-                mfma_all(ks & 1, act);
-            }
-            wait_tiles_in_flight<Cfg::kLoadsPerTile, kStages - 2>(KT - 2 - kt); // tiles after kt+1 may stay in flight
-            lds_barrier();
-            read_frags(kt + 1 < KT ? kt + 1 : kt, 0, 0, act); // the last one re-reads a valid stage; unused
-            mfma_all((kKSteps - 1) & 1, act);
-        }
+        MOE_WAIT_VMCNT(0); // the zero-byte loads past the last tile still write LDS: let them finish
     };
     // rows of the segment inside this wavefront's part of the tile -> active 32-row blocks
     {
