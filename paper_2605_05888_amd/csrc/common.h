@@ -36,9 +36,14 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
 }
 
+// Two fp32 -> one register of two bf16 (lo in the low half), round-to-nearest-even in hardware
+// (v_cvt_pk_bf16_f32).
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

@@ -25,86 +25,120 @@ namespace moe {
 // tile table
 // ------------------------------------------------------------------------
 constexpr int kSchedThreads = 256;
+// relative cost of a tile of a one-row-tile expert and of a full tile, for sharing out the workgroup slots
+#ifndef MOE_LIGHT_COST
+#define MOE_LIGHT_COST 3
+#endif
+#ifndef MOE_HEAVY_MIN
+#define MOE_HEAVY_MIN 2
+#endif
+constexpr int kLightCost = MOE_LIGHT_COST, kHeavyCost = 7;
 
-// table[L] for L in [0, num_tiles): order = expert, then column tile, then row tile.
+// Experts come in two classes: "heavy" ones with two row tiles or more, whose weight tiles are
+// shared by several workgroups and whose tiles are bound by the matrix cores, and "light" ones
+// (at most BM rows), whose tiles stream their weights from memory once and wait for them.  Each
+// class forms a stream of tiles (order: expert, then column tile, then row tile); the table holds
+// stream 0 (heavy), then stream 1 (light).  The GEMM's persistent workgroups draw from both.
+__device__ __forceinline__ int32_t clamped_rows(const int32_t *seg_offsets, int e, int64_t M, int64_t &lo)
+{
+    int64_t hi = seg_offsets[e + 1];
+    lo = seg_offsets[e];
+    lo = lo < 0 ? 0 : (lo > M ? M : lo);
+    hi = hi < lo ? lo : (hi > M ? M : hi);
+    return (int32_t)(hi - lo);
+}
+
 __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
     const int32_t *__restrict__ seg_offsets, int E_local, int64_t M, int BM, int n_tiles,
     int max_tiles, TileTableHeader *__restrict__ hdr, TileEntry *__restrict__ table)
 {
-    __shared__ int32_t start[MOE_MAX_EXPERTS + 1]; // first tile of each expert
-    __shared__ int32_t wave_tot[kSchedThreads / kWave];
+    __shared__ int32_t start[2][MOE_MAX_EXPERTS + 1]; // first tile of each expert in the heavy [0] / light [1] stream
+    __shared__ int32_t wave_tot[2][kSchedThreads / kWave];
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-    // exclusive scan of tiles per expert; thread owns a contiguous run of experts
+    // exclusive scans of tiles per expert; a thread owns a contiguous run of experts
     const int per = (E_local + kSchedThreads - 1) / kSchedThreads;
     const int e_lo = tid * per;
-    int32_t mine = 0;
+    int32_t mine[2] = {0, 0};
     for (int j = 0; j < per; ++j) {
-        int e = e_lo + j;
+        const int e = e_lo + j;
         if (e < E_local) {
-            int64_t lo = seg_offsets[e], hi = seg_offsets[e + 1];
-            lo = lo < 0 ? 0 : (lo > M ? M : lo);
-            hi = hi < lo ? lo : (hi > M ? M : hi);
-            mine += (int32_t)((hi - lo + BM - 1) / BM) * n_tiles;
+            int64_t lo;
+            const int m_tiles = (clamped_rows(seg_offsets, e, M, lo) + BM - 1) / BM;
+            mine[m_tiles >= MOE_HEAVY_MIN ? 0 : 1] += m_tiles * n_tiles;
         }
     }
-    int32_t inc = mine;
+    int32_t inc[2] = {mine[0], mine[1]};
     for (int d = 1; d < kWave; d <<= 1) {
-        int32_t t = __shfl_up(inc, d);
-        if (lane >= d)
-            inc += t;
-    }
-    if (lane == kWave - 1)
-        wave_tot[wave] = inc;
-    __syncthreads();
-    int32_t base = 0;
-    for (int w = 0; w < wave; ++w)
-        base += wave_tot[w];
-    int32_t run = base + inc - mine;
-    for (int j = 0; j < per; ++j) {
-        int e = e_lo + j;
-        if (e < E_local) {
-            int64_t lo = seg_offsets[e], hi = seg_offsets[e + 1];
-            lo = lo < 0 ? 0 : (lo > M ? M : lo);
-            hi = hi < lo ? lo : (hi > M ? M : hi);
-            start[e] = run;
-            run += (int32_t)((hi - lo + BM - 1) / BM) * n_tiles;
+        const int32_t t0 = __shfl_up(inc[0], d), t1 = __shfl_up(inc[1], d);
+        if (lane >= d) {
+            inc[0] += t0;
+            inc[1] += t1;
         }
     }
-    __syncthreads();
-    if (tid == 0) {
-        // total = start[last] + tiles(last)
-        int e = E_local - 1;
-        int64_t lo = seg_offsets[e], hi = seg_offsets[e + 1];
-        lo = lo < 0 ? 0 : (lo > M ? M : lo);
-        hi = hi < lo ? lo : (hi > M ? M : hi);
-        start[E_local] = start[e] + (int32_t)((hi - lo + BM - 1) / BM) * n_tiles;
+    if (lane == kWave - 1) {
+        wave_tot[0][wave] = inc[0];
+        wave_tot[1][wave] = inc[1];
     }
     __syncthreads();
-    int32_t total = start[E_local];
-    if (total > max_tiles)
-        total = max_tiles; // cannot happen for monotone offsets within [0, M]
-    if (blockIdx.x == 0 && tid == 0)
-        hdr->num_tiles = total;
+    int32_t run[2] = {inc[0] - mine[0], inc[1] - mine[1]};
+    for (int w = 0; w < wave; ++w) {
+        run[0] += wave_tot[0][w];
+        run[1] += wave_tot[1][w];
+    }
+    for (int j = 0; j < per; ++j) {
+        const int e = e_lo + j;
+        if (e < E_local) {
+            int64_t lo;
+            const int m_tiles = (clamped_rows(seg_offsets, e, M, lo) + BM - 1) / BM;
+            start[0][e] = run[0];
+            start[1][e] = run[1];
+            run[m_tiles >= MOE_HEAVY_MIN ? 0 : 1] += m_tiles * n_tiles;
+        }
+    }
+    if (tid == kSchedThreads - 1) { // the last thread's running sums are the totals
+        start[0][E_local] = run[0];
+        start[1][E_local] = run[1];
+    }
+    __syncthreads();
+    int32_t len[2] = {start[0][E_local], start[1][E_local]};
+    if (len[0] + len[1] > max_tiles) { // cannot happen for monotone offsets within [0, M]
+        len[0] = len[0] < max_tiles ? len[0] : max_tiles;
+        len[1] = max_tiles - len[0];
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+        hdr->len[0] = len[0];
+        hdr->len[1] = len[1];
+        // share of the workgroup slots that take the light stream first: the light tiles' share of
+        // the work, a light tile counted as kLightCost/kHeavyCost of a heavy one
+        const int64_t wl = (int64_t)len[1] * kLightCost, wh = (int64_t)len[0] * kHeavyCost;
+        hdr->light_slots = wl + wh > 0 ? (int32_t)((32 * wl + (wl + wh) / 2) / (wl + wh)) : 0;
+        hdr->done = 0;
+        for (int s = 0; s < 2; ++s)
+            for (int x = 0; x < kXcds; ++x)
+                hdr->next[s][x] = 0;
+    }
+    const int32_t total = len[0] + len[1];
     for (int L = blockIdx.x * kSchedThreads + tid; L < total; L += gridDim.x * kSchedThreads) {
-        int lo_e = 0, hi_e = E_local; // last e with start[e] <= L
+        const int c = L < len[0] ? 0 : 1;
+        const int32_t pos = L - (c ? len[0] : 0); // position in the stream
+        int lo_e = 0, hi_e = E_local;             // last e with start[c][e] <= pos: the expert that owns it
         while (hi_e - lo_e > 1) {
-            int mid = (lo_e + hi_e) >> 1;
-            if (start[mid] <= L)
+            const int mid = (lo_e + hi_e) >> 1;
+            if (start[c][mid] <= pos)
                 lo_e = mid;
             else
                 hi_e = mid;
         }
         const int e = lo_e;
-        int64_t lo = seg_offsets[e], hi = seg_offsets[e + 1];
-        lo = lo < 0 ? 0 : (lo > M ? M : lo);
-        hi = hi < lo ? lo : (hi > M ? M : hi);
-        const int m_tiles = (int)((hi - lo + BM - 1) / BM);
-        const int local = L - start[e];
+        int64_t lo;
+        const int32_t n_rows_e = clamped_rows(seg_offsets, e, M, lo);
+        const int m_tiles = (n_rows_e + BM - 1) / BM;
+        const int local = pos - start[c][e];
         TileEntry t;
         t.expert = e;
         t.n_tile = local / m_tiles;
         t.m0 = (int32_t)lo + (local % m_tiles) * BM;
-        t.m_end = (int32_t)hi;
+        t.m_end = (int32_t)lo + n_rows_e;
         table[L] = t;
     }
 }
@@ -200,11 +234,11 @@ static FfnPlan make_plan(int64_t M, int64_t H, int64_t F, int E_local)
     p.off_a = o;
     o = align_up(o + (size_t)M * F * 2, 256);
     p.off_hdr1 = o;
-    o += 256;
+    o += kTileTableHeaderBytes;
     p.off_tab1 = o;
     o = align_up(o + (size_t)p.max_m_tiles * p.n_tiles1 * sizeof(TileEntry), 256);
     p.off_hdr2 = o;
-    o += 256;
+    o += kTileTableHeaderBytes;
     p.off_tab2 = o;
     o = align_up(o + (size_t)p.max_m_tiles * p.n_tiles2 * sizeof(TileEntry), 256);
     p.total = o;
@@ -225,10 +259,27 @@ size_t ffn_workspace_bytes(int64_t M, int64_t H, int64_t F, int E_local, int dty
 #define MOE_DISTA64 0x0044
 #define MOE_DISTB64 0x4400
 #endif
+// workgroup slots of the device: compute units times the workgroups of this kernel a unit holds
+static int workgroup_slots(int per_cu)
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+            return kXcds * 32;
+        cus = prop.multiProcessorCount;
+    }
+    int g = cus * per_cu / kXcds * kXcds; // whole rounds over the XCDs
+    if (g > kMaxGemmWorkgroups)
+        g = kMaxGemmWorkgroups / kXcds * kXcds;
+    return g < kXcds ? kXcds : g;
+}
+
 template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK, int kUnits, int kDistA, int kDistB>
 static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const uint16_t *B0,
-                        const uint16_t *B1, uint16_t *C, const TileTableHeader *hdr,
-                        const TileEntry *table, int max_tiles, int patch, hipStream_t st)
+                        const uint16_t *B1, uint16_t *C, TileTableHeader *hdr,
+                        const TileEntry *table, int patch, hipStream_t st)
 {
     using Cfg = GemmCfg<BM, BN, WM, WN, kSwiglu, kBK, kUnits>;
     auto kern = grouped_gemm_bf16<BM, BN, WM, WN, kSwiglu, kBK, kUnits, kDistA, kDistB>;
@@ -238,9 +289,8 @@ static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const 
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::kLdsBytes);
         attr_set = true;
     }
-    // grid covers the worst-case tile count, rounded up to whole patches over all XCDs
-    const int group = patch * kXcds;
-    const int grid = (int)ceil_div(max_tiles, group) * group;
+    // persistent grid: the workgroups draw their tiles from the table's counters
+    const int grid = workgroup_slots(BM * BN <= 256 * 128 ? 2 : 1);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::kThreads), Cfg::kLdsBytes, st, A, M, Kdim, Ndim, B0,
                        B1, C, hdr, table, patch);
 }
@@ -311,9 +361,9 @@ int launch_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t 
     const uint16_t *xpb = static_cast<const uint16_t *>(xp);
     const uint16_t *wg = static_cast<const uint16_t *>(W_gate), *wu = static_cast<const uint16_t *>(W_up);
     if (p.big)
-        launch_gemm<256, 256, 2, 2, true, 64, MOE_UNITS64, MOE_DISTA64, MOE_DISTB64>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
+        launch_gemm<256, 256, 2, 2, true, 64, MOE_UNITS64, MOE_DISTA64, MOE_DISTB64>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, kPatch, st);
     else
-        launch_gemm<128, 128, 2, 2, true, 32, 8, 0x20, 0x02>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, k.max1, kPatch, st);
+        launch_gemm<128, 128, 2, 2, true, 32, 8, 0x20, 0x02>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, kPatch, st);
     return check_launch("moe_ffn_gate_up");
 }
 
@@ -331,9 +381,9 @@ int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     const uint16_t *wd = static_cast<const uint16_t *>(W_down);
     uint16_t *yb = static_cast<uint16_t *>(y);
     if (p.big)
-        launch_gemm<256, 256, 2, 2, false, 64, MOE_UNITS64, MOE_DISTA64, MOE_DISTB64>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
+        launch_gemm<256, 256, 2, 2, false, 64, MOE_UNITS64, MOE_DISTA64, MOE_DISTB64>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, kPatch, st);
     else
-        launch_gemm<128, 128, 2, 2, false, 32, 8, 0x20, 0x02>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, k.max2, kPatch, st);
+        launch_gemm<128, 128, 2, 2, false, 32, 8, 0x20, 0x02>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, kPatch, st);
     return check_launch("moe_ffn_down");
 }
 

@@ -43,25 +43,36 @@ struct TileEntry {
     int32_t n_tile; // column tile
 };
 
-struct TileTableHeader {
-    int32_t num_tiles;
-    int32_t pad[3];
-};
-
 constexpr int kXcds = 8;
+constexpr int kMaxGemmWorkgroups = 896; // workgroups of the persistent grid (ticket words of a table)
 
-// Workgroup id -> position in the tile order.  Ids are dealt round-robin to the
-// 8 XCDs; each XCD takes runs of `patch` consecutive tiles so its L2 sees tiles
-// that share weight and activation rows.
-__device__ __forceinline__ int tile_of_workgroup(int id, int patch)
+// Head of a tile table.  The table holds two streams of tiles, one after the other: stream 0 the
+// tiles of experts with two row tiles or more (their weight tiles are shared by several
+// workgroups and the matrix cores bound them), stream 1 the tiles of experts with one row tile
+// (they stream their weights from memory once and mostly wait for them).
+struct TileTableHeader {
+    int32_t len[2];         // tiles in each stream; stream s starts at entry (s ? len[0] : 0)
+    int32_t light_slots;    // of the 32 workgroup slots an XCD has, how many take stream 1 first
+    int32_t done;           // workgroups that have left the kernel (the last one resets the counters)
+    int32_t pad[4];
+    int32_t next[2][kXcds]; // per stream and XCD: tickets handed out so far
+    int32_t pad2[8];
+    int32_t ticket[kMaxGemmWorkgroups][8]; // per workgroup: tiles drawn by its first thread for all of it
+};
+constexpr size_t kTileTableHeaderBytes = 32768;
+static_assert(sizeof(TileTableHeader) <= kTileTableHeaderBytes, "header region");
+
+// Ticket j of an XCD -> position in a stream: each XCD takes runs of `patch` consecutive tiles, so
+// its L2 sees tiles that share weight and activation rows.
+__device__ __forceinline__ int stream_position(int xcd, int j, int patch)
 {
-    const int xcd = id % kXcds, j = id / kXcds;
     return (j / patch) * (patch * kXcds) + xcd * patch + (j % patch);
 }
 
+// silu(g) * u with the hardware reciprocal (1 ulp): the result is rounded to bf16 right after
 __device__ __forceinline__ float silu_mul(float g, float u)
 {
-    return g / (1.0f + __expf(-g)) * u;
+    return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
 }
 
 // XOR key of a tile row with kChunks 16-byte chunks: equal logical chunks of any 8 and
@@ -185,7 +196,7 @@ template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK, int kUnits, int
 __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void grouped_gemm_bf16(
     const uint16_t *__restrict__ A, int64_t M, int Kdim, int Ndim,
     const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
-    uint16_t *__restrict__ C, const TileTableHeader *__restrict__ hdr,
+    uint16_t *__restrict__ C, TileTableHeader *__restrict__ hdr,
     const TileEntry *__restrict__ table, int patch)
 {
 #if defined(__HIP_DEVICE_COMPILE__) // the body uses device-only types (buffer resources); the host pass only needs the stub
@@ -193,25 +204,62 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
     constexpr int kChunks = Cfg::kChunks, kRowBytes = Cfg::kRowBytes, kKSteps = Cfg::kKSteps;
     constexpr int kDepth = Cfg::kDepth, kAheadA = Cfg::kAheadA;
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-    const int L = tile_of_workgroup(blockIdx.x, patch);
-    if (L >= hdr->num_tiles)
-        return;
-    const TileEntry te = table[L];
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int wm = wave / WN, wn = wave % WN;
-    const int n0 = te.n_tile * Cfg::kOutCols;
+
+    // ---- tiles are handed out at run time.  The grid is persistent (one workgroup per
+    //      workgroup slot of the chip); workgroup ids are dealt round-robin to the XCDs, and a
+    //      workgroup takes tickets from its own XCD's counter of a stream, then from the others'.
+    //      Of the 32 slots of an XCD, hdr->light_slots prefer the stream of memory-bound tiles, the
+    //      rest the matrix-bound one, so both kinds run side by side from start to end and only a
+    //      bounded share of the chip queues up reads on the memory system at a time.
+    //      Thread 0 draws for the whole workgroup and passes the tile on through a word pair in
+    //      global memory (LDS is full and a register cannot cross wavefronts): {tile, sequence
+    //      number}, stored and loaded as one 8-byte unit.  A reader that finds an older sequence
+    //      number reads again, so nobody waits for the store to land and nobody acts on a stale tile.
+    const int xcd = blockIdx.x % kXcds;
+    int32_t *const my_ticket = hdr->ticket[blockIdx.x];
+    const int len0 = hdr->len[0], len1 = hdr->len[1];
+    const int slot = (blockIdx.x / kXcds) % 32, ls = hdr->light_slots;
+    const bool light_first = ((slot + 1) * ls) / 32 > (slot * ls) / 32;
+    auto fetch_tile = [&]() -> int { // thread 0 only
+#pragma unroll 1
+        for (int k = 0; k < 2; ++k) {
+            const int s = light_first ? 1 - k : k;
+            const int len = s ? len1 : len0;
+#pragma unroll 1
+            for (int i = 0; i < kXcds && len > 0; ++i) {
+                const int x = (xcd + i) % kXcds;
+                int32_t *ctr = &hdr->next[s][x];
+                if (k + i > 0) { // (the first choice is taken without looking: it is rarely spent)
+                    const int seen = __hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (stream_position(x, seen, patch) >= len)
+                        continue; // positions grow with the ticket: this counter is spent
+                }
+                const int j = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int p = stream_position(x, j, patch);
+                if (p < len)
+                    return (s ? len0 : 0) + p;
+            }
+        }
+        return -1;
+    };
+    // words 0, 1: the workgroup's first two tiles; words 2..5: two {tile, sequence number} pairs,
+    // used in turn, so that a draw stays readable until the draw after the next one is published
+    uint32_t seq = 0; // draws published so far
+    auto slot_of = [&](uint32_t q) { return reinterpret_cast<uint64_t *>(my_ticket + 2 + 2 * (q & 1)); };
+    auto publish = [&](int tile) { // thread 0 only
+        __hip_atomic_store(slot_of(seq), ((uint64_t)seq << 32) | (uint32_t)tile, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    };
+    auto read_slot = [&]() { return __hip_atomic_load(slot_of(seq), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
 
     // ---- global->LDS loads (buffer_load_dwordx4 ... lds): the lane at 16-byte position p of its
     //      row fetches chunk p ^ key(row).  Buffer addressing keeps the per-lane part of the address
-    //      in one 32-bit register (row offset inside the tile, fixed for the whole K loop); the tile
-    //      base sits in the scalar resource and the K offset in a scalar register.
+    //      in one 32-bit register (row offset inside the tile, the same for every tile and the whole
+    //      K loop); the tile base sits in the scalar resource and the K offset in a scalar register.
     const int ld_row = lane / kChunks, ld_pc = lane % kChunks;
-    //      Rows past the end of the segment (and columns past Ndim) lie beyond the resource's byte
-    //      count: the bounds check returns zeros for them without touching memory.
-    const int64_t rows_left = (int64_t)te.m_end - te.m0; // >= 1
-    const int64_t a_bytes = (rows_left < BM ? rows_left : BM) * (int64_t)Kdim * 2;
-    const uint16_t *a_base = A + (int64_t)te.m0 * Kdim;
     int a_off[Cfg::kAGroups];
 #pragma unroll
     for (int g = 0; g < Cfg::kAGroups; ++g) {
@@ -220,10 +268,6 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
     }
     // B rows of one wavefront (kSwiglu): first half gate columns, second half the same up columns.
     // A load group never straddles the two halves, so its resource is wave-uniform.
-    const int cols_left = Ndim - n0; // >= 1
-    const int64_t b_bytes = (cols_left < Cfg::kOutCols ? cols_left : Cfg::kOutCols) * (int64_t)Kdim * 2;
-    const uint16_t *b0_base = B0 + ((int64_t)te.expert * Ndim + n0) * Kdim;
-    const uint16_t *b1_base = (kSwiglu ? B1 : B0) + ((int64_t)te.expert * Ndim + n0) * Kdim;
     int b_off[Cfg::kBGroups];
 #pragma unroll
     for (int g = 0; g < Cfg::kBGroups; ++g) {
@@ -238,38 +282,73 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
         b_off[g] = (col * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8)) * 2;
     }
     const int KT = Kdim / kBK;
-    // A K tile past the end of the reduction is "loaded" through a resource of zero bytes: every
-    // lane is out of range, nothing is fetched and zeros land in a unit nobody reads.  So the
-    // loop issues the same number of loads in every iteration and the vmcnt arithmetic below
-    // holds from the first tile to the last.
-    auto resource = [&](const uint16_t *base, int64_t bytes, int tile) {
-        return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(base), 0,
-                                                 tile < KT ? (unsigned)bytes : 0u, 0x00020000);
+    // With kDepth + kAheadA K tiles or more per output tile, the loads that would run past the
+    // end of a tile's reduction fetch the first K tiles of the workgroup's next tile, so that tile
+    // starts with its operands in LDS.  (Shorter reductions start every tile from scratch.)
+    const bool warm = KT >= kDepth + kAheadA;
+
+    // What the loads of a tile need.  Rows past the end of the segment (and columns past Ndim) lie
+    // beyond the byte counts: the bounds check returns zeros for them without touching memory; a
+    // count of zero turns every load of a tile that does not exist into such a no-op, so the loop
+    // issues the same number of loads in every iteration and the vmcnt arithmetic below holds
+    // from the first K tile to the last.
+    struct Operands {
+        const uint16_t *a, *b; // b: the gate (or only) weight rows; the up rows lie b1_delta further
+        uint32_t a_bytes, b_bytes;
+        int32_t m0, m_end, n0;
     };
+    const int64_t b1_delta = kSwiglu ? B1 - B0 : 0;
+    auto operands_of = [&](int tile) {
+        Operands o = {A, B0, 0u, 0u, 0, 0, 0};
+        if (tile >= 0) {
+            const TileEntry te = table[tile];
+            const int n0 = te.n_tile * Cfg::kOutCols;
+            const int64_t rows_left = (int64_t)te.m_end - te.m0; // >= 1
+            const int cols_left = Ndim - n0;                      // >= 1
+            o.a = A + (int64_t)te.m0 * Kdim;
+            o.a_bytes = (uint32_t)((rows_left < BM ? rows_left : BM) * (int64_t)Kdim * 2);
+            o.b = B0 + ((int64_t)te.expert * Ndim + n0) * Kdim;
+            o.b_bytes = (uint32_t)((cols_left < Cfg::kOutCols ? cols_left : Cfg::kOutCols) * (int64_t)Kdim * 2);
+            o.m0 = te.m0;
+            o.m_end = te.m_end;
+            o.n0 = n0;
+        }
+        return o;
+    };
+    Operands cur, nxt; // the tile being computed; the one whose first K tiles are fetched behind it
     using lds_ptr = __attribute__((address_space(3))) void *;
-    auto load_a_group = [&](int tile, int unit, int g) {
+    // K tile t of `cur`; past its last K tile (kTail only): K tile t - KT of `nxt`
+    auto load_a_group = [&](int t, int unit, int g, auto tail_tag) {
+        constexpr bool kTail = decltype(tail_tag)::value;
+        const bool here = !kTail || t < KT;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t *>(here ? cur.a : nxt.a), 0, here ? cur.a_bytes : nxt.a_bytes, 0x00020000);
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            resource(a_base, a_bytes, tile),
-            (lds_ptr)(lds + unit * Cfg::kUnitBytes + (wave * Cfg::kAGroups + g) * 1024), 16, a_off[g],
-            tile * (kBK * 2), 0, 0);
+            rs, (lds_ptr)(lds + unit * Cfg::kUnitBytes + (wave * Cfg::kAGroups + g) * 1024), 16, a_off[g],
+            (here ? t : t - KT) * (kBK * 2), 0, 0);
     };
-    auto load_b_group = [&](int tile, int unit, int g) {
+    auto load_b_group = [&](int t, int unit, int g, auto tail_tag) {
+        constexpr bool kTail = decltype(tail_tag)::value;
+        const bool here = !kTail || t < KT;
         const int r0 = (wave * Cfg::kBGroups + g) * Cfg::kGroupRows; // uniform
         const bool up = kSwiglu && (r0 % Cfg::kWaveN) >= Cfg::kWaveN / 2;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t *>((here ? cur.b : nxt.b) + (up ? b1_delta : 0)), 0,
+            here ? cur.b_bytes : nxt.b_bytes, 0x00020000);
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            resource(up ? b1_base : b0_base, b_bytes, tile),
-            (lds_ptr)(lds + unit * Cfg::kUnitBytes + (wave * Cfg::kBGroups + g) * 1024), 16, b_off[g],
-            tile * (kBK * 2), 0, 0);
+            rs, (lds_ptr)(lds + unit * Cfg::kUnitBytes + (wave * Cfg::kBGroups + g) * 1024), 16, b_off[g],
+            (here ? t : t - KT) * (kBK * 2), 0, 0);
     };
 
     // ---- the ring.  K tile t keeps its A rows in unit (2t) % kUnits and its B rows in unit
-    //      (2t+1) % kUnits.  `u` below is always the A unit of the tile being multiplied.
+    //      (2t+1) % kUnits, counting the K tiles of a workgroup's successive output tiles on (when
+    //      `warm`).  `u` below is always the A unit of the K tile being multiplied.
     auto wrap = [](int x) { return x >= kUnits ? x - kUnits : x; };
     auto unit_a = [&](int u, int ahead) { return wrap(u + (2 * ahead) % kUnits); };
     auto unit_b = [&](int u, int ahead) { return wrap(u + (2 * ahead + 1) % kUnits); };
 
-    // ---- load schedule.  The barrier that ends the reads of tile t opens a "window": the units of
-    //      tile t are free, and until the next barrier the loads of B(t + kDepth) and of
+    // ---- load schedule.  The barrier that ends the reads of K tile t opens a "window": the units
+    //      of tile t are free, and until the next barrier the loads of B(t + kDepth) and of
     //      A(t + kDepth + kAheadA) are issued, in kKSteps positions: position 0 under the last
     //      k-step of tile t, position p under k-step p-1 of tile t+1 (kDistB / kDistA say how many
     //      loads each position takes; B first, then A).  Spreading them keeps the four wavefronts
@@ -278,18 +357,20 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
     //      the A loads, which are needed one tile later when the ring is odd, fill the rest.
     static_assert(part_first(kDistA, kKSteps, kKSteps) == Cfg::kAGroups, "A loads of a window");
     static_assert(part_first(kDistB, kKSteps, kKSteps) == Cfg::kBGroups, "B loads of a window");
-    auto issue_position = [&](int t, int u, auto pos_tag) { // window opened by the barrier of tile t
+    auto issue_position = [&](int t, int u, auto pos_tag, auto tail_tag) { // window opened by the barrier of tile t
         constexpr int p = decltype(pos_tag)::value;
 #pragma unroll
         for (int g = part_first(kDistB, kKSteps, p); g < part_first(kDistB, kKSteps, p + 1); ++g)
-            load_b_group(t + kDepth, unit_b(u, kDepth), g);
+            load_b_group(t + kDepth, unit_b(u, kDepth), g, tail_tag);
 #pragma unroll
         for (int g = part_first(kDistA, kKSteps, p); g < part_first(kDistA, kKSteps, p + 1); ++g)
-            load_a_group(t + kDepth + kAheadA, unit_a(u, kDepth + kAheadA), g);
+            load_a_group(t + kDepth + kAheadA, unit_a(u, kDepth + kAheadA), g, tail_tag);
     };
     auto loads_at = [](int p) { return part_loads(kDistA, kKSteps, p) + part_loads(kDistB, kKSteps, p); };
     // loads that may still be in flight when a barrier needs the next tile complete
     constexpr int kInFlight = (kDepth - 2) * Cfg::kLoadsPerTile + window_tail(kDistA, kDistB, kKSteps, kAheadA == 0);
+    using tail_yes = std::integral_constant<bool, true>;
+    using tail_no = std::integral_constant<bool, false>;
 
     // ---- operand reads: lane (i = lane%32, kg = lane/32) reads chunk (2*ks + kg) of row i of a block.
     //      Block and wavefront offsets are multiples of 32 rows, so the key depends on i only, and
@@ -317,14 +398,6 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
     };
 
     f32x16 acc[Cfg::kBlkM][Cfg::kBlkN];
-#pragma unroll
-    for (int i = 0; i < Cfg::kBlkM; ++i)
-#pragma unroll
-        for (int j = 0; j < Cfg::kBlkN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                acc[i][j][r] = 0.0f;
-
     auto mfma_all = [&](int slot, auto act_tag) {
         constexpr int kAct = decltype(act_tag)::value;
 #pragma unroll
@@ -334,102 +407,187 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
     };
 
-    auto pipeline = [&](auto act) {
+    int u = 0;      // ring position: A unit of the K tile to multiply next
+    int after_next; // the tile after `nxt`, picked up from the ticket slot inside the K loop
+
+    // One output tile: K loop, then the epilogue.  On entry K tile 0 of `cur` is in LDS (everyone's
+    // loads, behind a barrier) and the windows before it have issued what they should.
+    auto run_tile = [&](auto act) {
         constexpr int kAct = decltype(act)::value;
         constexpr int kMfma = kAct * Cfg::kBlkN, kReads = kAct ? kAct + Cfg::kBlkN : 0;
-        // ---- prologue: everything the windows before tile 0 would have issued, then position 0
-        //      of the window before tile 0; tile 0 landed
 #pragma unroll
-        for (int t = 0; t + 1 < kDepth + kAheadA; ++t) {
+        for (int i = 0; i < Cfg::kBlkM; ++i)
 #pragma unroll
-            for (int g = 0; g < Cfg::kAGroups; ++g)
-                load_a_group(t, (2 * t) % kUnits, g);
-            if (t + 1 < kDepth) {
+            for (int j = 0; j < Cfg::kBlkN; ++j)
 #pragma unroll
-                for (int g = 0; g < Cfg::kBGroups; ++g)
-                    load_b_group(t, (2 * t + 1) % kUnits, g);
-            }
-        }
-        issue_position(-1, kUnits - 2, std::integral_constant<int, 0>{});
-        // in flight after B(0): tiles 1 .. kDepth-2, the A rows that run ahead, position 0
-        MOE_WAIT_VMCNT((kDepth - 2) * Cfg::kLoadsPerTile + kAheadA * Cfg::kAGroups + loads_at(0));
-        lds_barrier();
-        read_frags(0, 0, 0, act);
+                for (int r = 0; r < 16; ++r)
+                    acc[i][j][r] = 0.0f;
+        read_frags(u, 0, 0, act);
 
-        // k-step ks of tile kt (not its last): position ks+1 of the window goes out, the operands
+        // k-step ks of K tile kt (not its last): position ks+1 of the window goes out, the operands
         // of k-step ks+1 are read, all under this step's MFMAs
-        auto kstep = [&](int kt, int u, auto ks_tag) {
+        auto kstep = [&](int kt, auto ks_tag, auto tail_tag) {
             constexpr int ks = decltype(ks_tag)::value;
-            issue_position(kt - 1, wrap(u + kUnits - 2), std::integral_constant<int, ks + 1>{});
+            issue_position(kt - 1, wrap(u + kUnits - 2), std::integral_constant<int, ks + 1>{}, tail_tag);
             read_frags(u, ks + 1, (ks + 1) & 1, act);
             mfma_all(ks & 1, act);
             interleave_under_mfma<kMfma, kReads, loads_at(ks + 1)>();
         };
         // The body is branch free (a branch around the LDS reads would make the compiler wait for
         // them before MFMAs that do not need them).
-        int u = 0;
-        for (int kt = 0; kt < KT; ++kt) {
-            kstep(kt, u, std::integral_constant<int, 0>{});
+        auto ktile = [&](int kt, auto tail_tag) {
+            kstep(kt, std::integral_constant<int, 0>{}, tail_tag);
             if constexpr (kKSteps > 2) {
-                kstep(kt, u, std::integral_constant<int, 1>{});
-                kstep(kt, u, std::integral_constant<int, 2>{});
+                kstep(kt, std::integral_constant<int, 1>{}, tail_tag);
+                kstep(kt, std::integral_constant<int, 2>{}, tail_tag);
             }
             __builtin_amdgcn_sched_barrier(0); // keep this k-step's MFMAs above the waits
             MOE_WAIT_LGKM0();                  // my reads of tile kt are complete
             MOE_WAIT_VMCNT(kInFlight);         // my part of tile kt+1 has landed
             lds_barrier();                     // ... and everyone's; the units of tile kt are free
-            issue_position(kt, u, std::integral_constant<int, 0>{});
-            read_frags(unit_a(u, 1), 0, 0, act); // after the last tile: a unit of zeros, unused
+            issue_position(kt, u, std::integral_constant<int, 0>{}, tail_tag);
+            read_frags(unit_a(u, 1), 0, 0, act); // past the last K tile: the next output tile's, read again there
             mfma_all((kKSteps - 1) & 1, act);
             interleave_under_mfma<kMfma, kReads, loads_at(0)>();
             u = unit_a(u, 1);
+        };
+        // the last kDepth + kAheadA K tiles look past the end of this tile's reduction
+        const int k_split = KT - (kDepth + kAheadA);
+        if (k_split > 0)
+            ktile(0, tail_no{});
+        else
+            ktile(0, tail_yes{});
+        // The tile after `nxt`: thread 0 stored it before it reached the barrier of K tile 0.  The
+        // load is left in flight and looked at after the K loop.
+        uint64_t slot_v = read_slot();
+        for (int kt = 1; kt < k_split; ++kt)
+            ktile(kt, tail_no{});
+        for (int kt = (k_split > 1 ? k_split : 1); kt < KT; ++kt)
+            ktile(kt, tail_yes{});
+        // (if the store had not landed when the load ran, the sequence number is an older one)
+        while (__builtin_amdgcn_readfirstlane((uint32_t)(slot_v >> 32)) != seq)
+            slot_v = read_slot();
+        after_next = (int)__builtin_amdgcn_readfirstlane((uint32_t)slot_v);
+
+        // ---- epilogue.  Block (i, j), register r of lane l:
+        //      output row    m = i*32 + l%32               (within the wavefront's rows)
+        //      output column n = j*32 + 8*(r/4) + 4*(l/32) + r%4
+        int m_lane = lane % 32, n_lane = (lane / 32) * 4;
+        // opaque to the optimiser: otherwise every column offset derived from them is kept in a
+        // register of its own across the whole persistent loop
+        asm volatile("" : "+v"(m_lane), "+v"(n_lane));
+        constexpr int kOutBlkN = kSwiglu ? Cfg::kBlkN / 2 : Cfg::kBlkN;
+#pragma unroll
+        for (int i = 0; i < kAct; ++i) {
+            const int64_t m = (int64_t)cur.m0 + wm * Cfg::kWaveM + i * 32 + m_lane;
+            if (m >= cur.m_end)
+                continue;
+            uint16_t *crow = C + m * Ndim;
+#pragma unroll
+            for (int j = 0; j < kOutBlkN; ++j) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = cur.n0 + wn * (kOutBlkN * 32) + j * 32 + q * 8 + n_lane;
+                    if (col >= Ndim)
+                        continue;
+                    float v[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        v[t] = kSwiglu ? silu_mul(acc[i][j][q * 4 + t], acc[i][j + kOutBlkN][q * 4 + t])
+                                       : acc[i][j][q * 4 + t];
+                    u32x2 o;
+                    o[0] = pack_bf16x2(v[0], v[1]);
+                    o[1] = pack_bf16x2(v[2], v[3]);
+                    *reinterpret_cast<u32x2 *>(crow + col) = o;
+                }
+            }
         }
-        MOE_WAIT_VMCNT(0); // the zero-byte loads past the last tile still write LDS: let them finish
     };
-    // rows of the segment inside this wavefront's part of the tile -> active 32-row blocks
-    {
-        const int64_t rows = (int64_t)te.m_end - ((int64_t)te.m0 + wm * Cfg::kWaveM);
+
+    // ---- the workgroup's first three tiles.  The words still hold what an earlier launch left
+    //      there, so these stores have to be in memory before anyone looks.
+    seq = 1;
+    if (tid == 0) {
+        int t = 0;
+#pragma unroll 1
+        for (int w = 0; w < 3; ++w) {
+            t = t >= 0 ? fetch_tile() : -1;
+            if (w < 2)
+                __hip_atomic_store(my_ticket + w, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else
+                publish(t);
+        }
+    }
+    MOE_WAIT_VMCNT(0);
+    __syncthreads();
+    int cur_t = __builtin_amdgcn_readfirstlane(
+        __hip_atomic_load(my_ticket + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    int nxt_t = __builtin_amdgcn_readfirstlane(
+        __hip_atomic_load(my_ticket + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    bool primed = false; // K tile 0 of `cur` is in LDS already
+    while (cur_t >= 0) {
+        if (!primed) {
+            cur = operands_of(cur_t);
+            nxt = operands_of(warm ? nxt_t : -1);
+            // everything the windows before K tile 0 would have issued, then position 0 of the
+            // window before it; K tile 0 landed
+            u = 0;
+#pragma unroll
+            for (int t = 0; t + 1 < kDepth + kAheadA; ++t) {
+#pragma unroll
+                for (int g = 0; g < Cfg::kAGroups; ++g)
+                    load_a_group(t, (2 * t) % kUnits, g, tail_yes{});
+                if (t + 1 < kDepth) {
+#pragma unroll
+                    for (int g = 0; g < Cfg::kBGroups; ++g)
+                        load_b_group(t, (2 * t + 1) % kUnits, g, tail_yes{});
+                }
+            }
+            issue_position(-1, kUnits - 2, std::integral_constant<int, 0>{}, tail_yes{});
+            // in flight after B(0): tiles 1 .. kDepth-2, the A rows that run ahead, position 0
+            MOE_WAIT_VMCNT((kDepth - 2) * Cfg::kLoadsPerTile + kAheadA * Cfg::kAGroups + loads_at(0));
+            lds_barrier();
+        }
+        // rows of the segment inside this wavefront's part of the tile -> active 32-row blocks
+        const int64_t rows = (int64_t)cur.m_end - ((int64_t)cur.m0 + wm * Cfg::kWaveM);
         const int active = rows <= 0 ? 0 : (rows >= Cfg::kWaveM ? Cfg::kBlkM : (int)((rows + 31) / 32));
         if (active == Cfg::kBlkM)
-            pipeline(std::integral_constant<int, Cfg::kBlkM>{});
+            run_tile(std::integral_constant<int, Cfg::kBlkM>{});
         else if (active == 0)
-            pipeline(std::integral_constant<int, 0>{});
+            run_tile(std::integral_constant<int, 0>{});
         else if (active == 1)
-            pipeline(std::integral_constant<int, 1>{});
+            run_tile(std::integral_constant<int, 1>{});
         else if (Cfg::kBlkM > 2 && active == 2)
-            pipeline(std::integral_constant<int, (Cfg::kBlkM > 2 ? 2 : 1)>{});
+            run_tile(std::integral_constant<int, (Cfg::kBlkM > 2 ? 2 : 1)>{});
         else
-            pipeline(std::integral_constant<int, (Cfg::kBlkM > 3 ? 3 : 1)>{});
-    }
+            run_tile(std::integral_constant<int, (Cfg::kBlkM > 3 ? 3 : 1)>{});
 
-    // ---- epilogue.  Block (i, j), register r of lane l:
-    //      output row    m = i*32 + l%32               (within the wavefront's rows)
-    //      output column n = j*32 + 8*(r/4) + 4*(l/32) + r%4
-    const int m_lane = lane % 32, n_lane = (lane / 32) * 4;
-    constexpr int kOutBlkN = kSwiglu ? Cfg::kBlkN / 2 : Cfg::kBlkN;
+        if (!warm) {
+            MOE_WAIT_VMCNT(0); // the no-op loads past the last K tile still write LDS: let them finish
+            lds_barrier();     // before anyone refills those units
+        }
+        // Thread 0 draws the tile that will follow `after_next` and leaves it in the other slot under
+        // the next sequence number; the others look there after the next tile's first barrier.
+        ++seq;
+        if (tid == 0)
+            publish(after_next >= 0 ? fetch_tile() : -1);
+        cur_t = nxt_t;
+        nxt_t = after_next;
+        if (warm) {
+            cur = nxt; // its first K tiles are in LDS or on their way
+            nxt = operands_of(nxt_t);
+            primed = true;
+        }
+    }
+    MOE_WAIT_VMCNT(0);
+    // the last workgroup to leave resets the counters for the next launch over this table
+    if (tid == 0) {
+        if (__hip_atomic_fetch_add(&hdr->done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1) {
 #pragma unroll
-    for (int i = 0; i < Cfg::kBlkM; ++i) {
-        const int64_t m = (int64_t)te.m0 + wm * Cfg::kWaveM + i * 32 + m_lane;
-        if (m >= te.m_end)
-            continue;
-        uint16_t *crow = C + m * Ndim;
-#pragma unroll
-        for (int j = 0; j < kOutBlkN; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int col = n0 + wn * (kOutBlkN * 32) + j * 32 + q * 8 + n_lane;
-                if (col >= Ndim)
-                    continue;
-                float v[4];
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    v[t] = kSwiglu ? silu_mul(acc[i][j][q * 4 + t], acc[i][j + kOutBlkN][q * 4 + t])
-                                   : acc[i][j][q * 4 + t];
-                u32x2 o;
-                o[0] = pack_bf16x2(v[0], v[1]);
-                o[1] = pack_bf16x2(v[2], v[3]);
-                *reinterpret_cast<u32x2 *>(crow + col) = o;
-            }
+            for (int s = 0; s < 2; ++s)
+                for (int x = 0; x < kXcds; ++x)
+                    __hip_atomic_store(&hdr->next[s][x], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&hdr->done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 #endif
