@@ -29,16 +29,21 @@ constexpr int kSchedThreads = 256;
 #ifndef MOE_LIGHT_COST
 #define MOE_LIGHT_COST 3
 #endif
-#ifndef MOE_HEAVY_MIN
-#define MOE_HEAVY_MIN 2
-#endif
 constexpr int kLightCost = MOE_LIGHT_COST, kHeavyCost = 7;
+#ifndef MOE_ORDER_BLOCK
+#define MOE_ORDER_BLOCK 4
+#endif
+constexpr int kOrderBlock = MOE_ORDER_BLOCK;
+// experts with at most this many rows go through the shallow tile geometry
+#ifndef MOE_LIGHT_ROWS
+#define MOE_LIGHT_ROWS 64
+#endif
 
-// Experts come in two classes: "heavy" ones with two row tiles or more, whose weight tiles are
-// shared by several workgroups and whose tiles are bound by the matrix cores, and "light" ones
-// (at most BM rows), whose tiles stream their weights from memory once and wait for them.  Each
-// class forms a stream of tiles (order: expert, then column tile, then row tile); the table holds
-// stream 0 (heavy), then stream 1 (light).  The GEMM's persistent workgroups draw from both.
+// Experts come in two classes: "light" ones with at most `light_rows` rows, whose one row tile
+// streams its weights from memory once and mostly waits for them (the GEMM has a shallow, deeply
+// prefetching tile geometry for those), and the rest.  Each class forms a stream of tiles (order:
+// expert, then column tile, then row tile); the table holds stream 0 (the rest), then stream 1
+// (light).  The GEMM's persistent workgroups draw from both.
 __device__ __forceinline__ int32_t clamped_rows(const int32_t *seg_offsets, int e, int64_t M, int64_t &lo)
 {
     int64_t hi = seg_offsets[e + 1];
@@ -49,7 +54,7 @@ __device__ __forceinline__ int32_t clamped_rows(const int32_t *seg_offsets, int 
 }
 
 __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
-    const int32_t *__restrict__ seg_offsets, int E_local, int64_t M, int BM, int n_tiles,
+    const int32_t *__restrict__ seg_offsets, int E_local, int64_t M, int BM, int n_tiles, int light_rows,
     int max_tiles, TileTableHeader *__restrict__ hdr, TileEntry *__restrict__ table)
 {
     __shared__ int32_t start[2][MOE_MAX_EXPERTS + 1]; // first tile of each expert in the heavy [0] / light [1] stream
@@ -63,8 +68,8 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
         const int e = e_lo + j;
         if (e < E_local) {
             int64_t lo;
-            const int m_tiles = (clamped_rows(seg_offsets, e, M, lo) + BM - 1) / BM;
-            mine[m_tiles >= MOE_HEAVY_MIN ? 0 : 1] += m_tiles * n_tiles;
+            const int32_t rows = clamped_rows(seg_offsets, e, M, lo);
+            mine[rows <= light_rows ? 1 : 0] += (rows + BM - 1) / BM * n_tiles;
         }
     }
     int32_t inc[2] = {mine[0], mine[1]};
@@ -89,10 +94,10 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
         const int e = e_lo + j;
         if (e < E_local) {
             int64_t lo;
-            const int m_tiles = (clamped_rows(seg_offsets, e, M, lo) + BM - 1) / BM;
+            const int32_t rows = clamped_rows(seg_offsets, e, M, lo);
             start[0][e] = run[0];
             start[1][e] = run[1];
-            run[m_tiles >= MOE_HEAVY_MIN ? 0 : 1] += m_tiles * n_tiles;
+            run[rows <= light_rows ? 1 : 0] += (rows + BM - 1) / BM * n_tiles;
         }
     }
     if (tid == kSchedThreads - 1) { // the last thread's running sums are the totals
@@ -133,11 +138,22 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
         int64_t lo;
         const int32_t n_rows_e = clamped_rows(seg_offsets, e, M, lo);
         const int m_tiles = (n_rows_e + BM - 1) / BM;
+        // Inside an expert the tiles go in blocks of kOrderBlock x kOrderBlock (row tiles x column
+        // tiles): the 16 tiles an XCD takes together then share 4 weight tiles and 4 activation
+        // tiles in its L2, instead of one and 16.
         const int local = pos - start[c][e];
+        const int band_tiles = kOrderBlock * n_tiles; // tiles of a full band of kOrderBlock row tiles
+        int rb = local / band_tiles;
+        const int last_band = (m_tiles - 1) / kOrderBlock;
+        rb = rb > last_band ? last_band : rb;
+        const int h = m_tiles - rb * kOrderBlock < kOrderBlock ? m_tiles - rb * kOrderBlock : kOrderBlock;
+        const int in_band = local - rb * band_tiles;
+        const int cb = in_band / (kOrderBlock * h);
+        const int in_block = in_band - cb * kOrderBlock * h;
         TileEntry t;
         t.expert = e;
-        t.n_tile = local / m_tiles;
-        t.m0 = (int32_t)lo + (local % m_tiles) * BM;
+        t.n_tile = cb * kOrderBlock + in_block / h;
+        t.m0 = (int32_t)lo + (rb * kOrderBlock + in_block % h) * BM;
         t.m_end = (int32_t)lo + n_rows_e;
         table[L] = t;
     }
@@ -211,8 +227,14 @@ __global__ __launch_bounds__(256) void ffn_f32_down(const float *__restrict__ a,
 // ------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------
+// Geometries.  Big: 256x256x64 tile, ring of 5 units (all 160 KiB of LDS); per window the 8 B loads
+// of a wavefront go out under the first two k-steps after the barrier, the 8 A loads under the
+// other two.  Shallow: 64x256x64 tile for experts with few rows, four (A, B) unit pairs, so that
+// three K tiles of weights are in flight while one is multiplied. 
+template <bool kSwiglu> using BigTile = GemmCfg<256, 256, 2, 2, kSwiglu, 64, 5, 0x0044, 0x4400, 0>;
+template <bool kSwiglu> using ShallowTile = GemmCfg<64, 256, 1, 4, kSwiglu, 64, 8, 0x1010, 0x2222, 1>;
+
 struct FfnPlan {
-    bool big;
     int BM, out_cols1, out_cols2;
     int n_tiles1, n_tiles2, max_m_tiles;
     size_t off_a, off_hdr1, off_tab1, off_hdr2, off_tab2, total;
@@ -223,10 +245,9 @@ static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static FfnPlan make_plan(int64_t M, int64_t H, int64_t F, int E_local)
 {
     FfnPlan p;
-    p.big = (M / (E_local > 0 ? E_local : 1)) >= 192;
-    p.BM = p.big ? 256 : 128;
-    p.out_cols1 = p.big ? 128 : 64; // GEMM1 writes BN/2 columns of `a` per tile
-    p.out_cols2 = p.big ? 256 : 128;
+    p.BM = BigTile<true>::BM;
+    p.out_cols1 = BigTile<true>::kOutCols; // GEMM1 writes BN/2 columns of `a` per tile
+    p.out_cols2 = BigTile<false>::kOutCols;
     p.n_tiles1 = (int)ceil_div(F, p.out_cols1);
     p.n_tiles2 = (int)ceil_div(H, p.out_cols2);
     p.max_m_tiles = (int)(M / p.BM) + E_local;
@@ -252,13 +273,6 @@ size_t ffn_workspace_bytes(int64_t M, int64_t H, int64_t F, int E_local, int dty
     return make_plan(M, H, F, E_local).total;
 }
 
-// 256x256x64 tile: ring of 5 units (all 160 KiB of LDS); per window the 8 B loads of a wavefront go
-// out under the first two k-steps after the barrier, the 8 A loads under the other two.
-#ifndef MOE_UNITS64
-#define MOE_UNITS64 5
-#define MOE_DISTA64 0x0044
-#define MOE_DISTB64 0x4400
-#endif
 // workgroup slots of the device: compute units times the workgroups of this kernel a unit holds
 static int workgroup_slots(int per_cu)
 {
@@ -276,23 +290,25 @@ static int workgroup_slots(int per_cu)
     return g < kXcds ? kXcds : g;
 }
 
-template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK, int kUnits, int kDistA, int kDistB>
+template <class Main, class Light, bool kSwiglu>
 static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const uint16_t *B0,
                         const uint16_t *B1, uint16_t *C, TileTableHeader *hdr,
                         const TileEntry *table, int patch, hipStream_t st)
 {
-    using Cfg = GemmCfg<BM, BN, WM, WN, kSwiglu, kBK, kUnits>;
-    auto kern = grouped_gemm_bf16<BM, BN, WM, WN, kSwiglu, kBK, kUnits, kDistA, kDistB>;
+    auto kern = grouped_gemm_bf16<Main, Light, kSwiglu>;
+    size_t lds_bytes = Main::kLdsBytes;
+    if constexpr (!std::is_void<Light>::value)
+        lds_bytes = lds_bytes > Light::kLdsBytes ? lds_bytes : Light::kLdsBytes;
     static bool attr_set = false; // raising the dynamic LDS limit is idempotent
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::kLdsBytes);
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         attr_set = true;
     }
     // persistent grid: the workgroups draw their tiles from the table's counters
-    const int grid = workgroup_slots(BM * BN <= 256 * 128 ? 2 : 1);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::kThreads), Cfg::kLdsBytes, st, A, M, Kdim, Ndim, B0,
-                       B1, C, hdr, table, patch);
+    const int grid = workgroup_slots(Main::kLdsBytes <= 80 * 1024 ? 2 : 1);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(Main::kThreads), lds_bytes, st, A, M, Kdim, Ndim, B0, B1, C,
+                       hdr, table, patch);
 }
 
 int check_ffn_shape(int dtype, int64_t H, int64_t F)
@@ -304,7 +320,7 @@ int check_ffn_shape(int dtype, int64_t H, int64_t F)
     return MOE_OK;
 }
 
-// consecutive tiles each XCD takes at a time (see tile_of_workgroup)
+// consecutive tiles each XCD takes at a time (see stream_position)
 constexpr int kPatch = 16;
 
 struct FfnWorkspace {
@@ -337,10 +353,10 @@ int launch_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     const FfnPlan p = make_plan(M, H, F, E_local);
     const FfnWorkspace k = carve(p, ws);
     hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(k.max1, kSchedThreads)),
-                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles1, k.max1,
+                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles1, MOE_LIGHT_ROWS, k.max1,
                        k.hdr1, k.tab1);
     hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(k.max2, kSchedThreads)),
-                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles2, k.max2,
+                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles2, MOE_LIGHT_ROWS, k.max2,
                        k.hdr2, k.tab2);
     return check_launch("moe_ffn_schedule");
 }
@@ -360,10 +376,7 @@ int launch_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t 
     const FfnWorkspace k = carve(p, ws);
     const uint16_t *xpb = static_cast<const uint16_t *>(xp);
     const uint16_t *wg = static_cast<const uint16_t *>(W_gate), *wu = static_cast<const uint16_t *>(W_up);
-    if (p.big)
-        launch_gemm<256, 256, 2, 2, true, 64, MOE_UNITS64, MOE_DISTA64, MOE_DISTB64>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, kPatch, st);
-    else
-        launch_gemm<128, 128, 2, 2, true, 32, 8, 0x20, 0x02>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, kPatch, st);
+    launch_gemm<BigTile<true>, ShallowTile<true>, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, kPatch, st);
     return check_launch("moe_ffn_gate_up");
 }
 
@@ -380,10 +393,7 @@ int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     const FfnWorkspace k = carve(p, ws);
     const uint16_t *wd = static_cast<const uint16_t *>(W_down);
     uint16_t *yb = static_cast<uint16_t *>(y);
-    if (p.big)
-        launch_gemm<256, 256, 2, 2, false, 64, MOE_UNITS64, MOE_DISTA64, MOE_DISTB64>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, kPatch, st);
-    else
-        launch_gemm<128, 128, 2, 2, false, 32, 8, 0x20, 0x02>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, kPatch, st);
+    launch_gemm<BigTile<false>, ShallowTile<false>, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, kPatch, st);
     return check_launch("moe_ffn_down");
 }
 

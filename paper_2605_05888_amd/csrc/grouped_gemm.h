@@ -163,8 +163,12 @@ constexpr int window_tail(int dist_a, int dist_b, int parts, bool a_needed)
     return after;
 }
 
-template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK, int kUnits>
+// One tile geometry: BM x BN output tile, WM x WN wavefronts, K tiles of kBK, LDS ring of kUnits
+// units, kDistA / kDistB the load schedule (see the kernel), kKind the tile stream it serves.
+template <int BM_, int BN_, int WM_, int WN_, bool kSwiglu, int kBK_, int kUnits_, int kDistA_, int kDistB_, int kKind_>
 struct GemmCfg {
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, kBK = kBK_, kUnits = kUnits_;
+    static constexpr int kDistA = kDistA_, kDistB = kDistB_, kKind = kKind_;
     static constexpr int kWaves = WM * WN;
     static constexpr int kThreads = kWaves * kWave;
     static constexpr int kWaveM = BM / WM;    // rows per wavefront
@@ -179,45 +183,56 @@ struct GemmCfg {
     static constexpr int kLoadsPerTile = kAGroups + kBGroups; // per lane, per K tile
     static constexpr int kKSteps = kBK / 16;
     static constexpr int kOutCols = kSwiglu ? BN / 2 : BN;
-    // LDS is a ring of kUnits units; a unit holds the A rows or the B rows of one K tile.
-    static constexpr int kUnitBytes = (BM > BN ? BM : BN) * kRowBytes;
+    // LDS is a ring of kUnits units; a unit holds the A rows or the B rows of one K tile.  With
+    // BM == BN all units have one size and the ring may be odd; otherwise the units come in
+    // (A, B) pairs and the ring is even.
+    static constexpr int kABytes = BM * kRowBytes, kBBytes = BN * kRowBytes;
     static constexpr int kDepth = kUnits / 2;  // K tiles whose B part fits besides the one in use
     static constexpr int kAheadA = kUnits % 2; // an odd ring lets the A loads run one tile further ahead
-    static constexpr size_t kLdsBytes = (size_t)kUnits * kUnitBytes;
+    static constexpr size_t kLdsBytes =
+        BM == BN ? (size_t)kUnits * kABytes : (size_t)(kUnits / 2) * (kABytes + kBBytes);
+    static constexpr int unit_base(int unit)
+    {
+        return BM == BN ? unit * kABytes : (unit >> 1) * (kABytes + kBBytes) + (unit & 1) * kABytes;
+    }
     static_assert(kBK == 32 || kBK == 64, "K tile");
-    static_assert(kUnits >= 4, "two K tiles at least");
+    static_assert(kUnits >= 4 && (BM == BN || kUnits % 2 == 0), "ring");
     static_assert(kWaveM % 32 == 0 && kWaveN % 32 == 0, "wave tile must be 32x32 blocks");
     static_assert(BM % (kGroupRows * kWaves) == 0 && BN % (kGroupRows * kWaves) == 0, "load groups");
     static_assert(!kSwiglu || kBlkN % 2 == 0, "gate and up halves");
     static_assert(kLoadsPerTile * (kDepth + kAheadA) <= 63, "vmcnt budget");
 };
 
-template <int BM, int BN, int WM, int WN, bool kSwiglu, int kBK, int kUnits, int kDistA, int kDistB>
-__global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void grouped_gemm_bf16(
+// Persistent grouped GEMM.  Main: the geometry of stream 0 (and of everything when there is no
+// second geometry); Light: the geometry of stream 1, tiles of experts with at most Light::BM rows,
+// or `void`.  Both geometries have the same workgroup size, BN and K tile.
+template <class Main, class Light, bool kSwiglu>
+__global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 : 1)) void grouped_gemm_bf16(
     const uint16_t *__restrict__ A, int64_t M, int Kdim, int Ndim,
     const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
     uint16_t *__restrict__ C, TileTableHeader *__restrict__ hdr,
     const TileEntry *__restrict__ table, int patch)
 {
 #if defined(__HIP_DEVICE_COMPILE__) // the body uses device-only types (buffer resources); the host pass only needs the stub
-    using Cfg = GemmCfg<BM, BN, WM, WN, kSwiglu, kBK, kUnits>;
-    constexpr int kChunks = Cfg::kChunks, kRowBytes = Cfg::kRowBytes, kKSteps = Cfg::kKSteps;
-    constexpr int kDepth = Cfg::kDepth, kAheadA = Cfg::kAheadA;
+    constexpr bool kTwo = !std::is_void<Light>::value;
+    if constexpr (kTwo)
+        static_assert(std::conditional_t<kTwo, Light, Main>::kBK == Main::kBK &&
+                          std::conditional_t<kTwo, Light, Main>::BN == Main::BN &&
+                          std::conditional_t<kTwo, Light, Main>::kThreads == Main::kThreads,
+                      "the two geometries share K tile, BN and workgroup size");
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-    const int wm = wave / WN, wn = wave % WN;
 
     // ---- tiles are handed out at run time.  The grid is persistent (one workgroup per
     //      workgroup slot of the chip); workgroup ids are dealt round-robin to the XCDs, and a
     //      workgroup takes tickets from its own XCD's counter of a stream, then from the others'.
     //      Of the 32 slots of an XCD, hdr->light_slots prefer the stream of memory-bound tiles, the
-    //      rest the matrix-bound one, so both kinds run side by side from start to end and only a
-    //      bounded share of the chip queues up reads on the memory system at a time.
-    //      Thread 0 draws for the whole workgroup and passes the tile on through a word pair in
-    //      global memory (LDS is full and a register cannot cross wavefronts): {tile, sequence
-    //      number}, stored and loaded as one 8-byte unit.  A reader that finds an older sequence
-    //      number reads again, so nobody waits for the store to land and nobody acts on a stale tile.
+    //      rest the matrix-bound one, so both kinds run side by side from start to end.
+    //      Thread 0 draws for the whole workgroup and passes the tile on through global memory
+    //      (LDS is full and a register cannot cross wavefronts): {tile, sequence number}, stored
+    //      and loaded as one 8-byte unit.  A reader that finds an older sequence number reads
+    //      again, so nobody waits for the store to land and nobody acts on a stale tile.
     const int xcd = blockIdx.x % kXcds;
     int32_t *const my_ticket = hdr->ticket[blockIdx.x];
     const int len0 = hdr->len[0], len1 = hdr->len[1];
@@ -245,6 +260,7 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
         }
         return -1;
     };
+    auto kind_of = [&](int tile) { return kTwo && tile >= len0 ? 1 : 0; };
     // words 0, 1: the workgroup's first two tiles; words 2..5: two {tile, sequence number} pairs,
     // used in turn, so that a draw stays readable until the draw after the next one is published
     uint32_t seq = 0; // draws published so far
@@ -254,6 +270,21 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
                            __HIP_MEMORY_SCOPE_AGENT);
     };
     auto read_slot = [&]() { return __hip_atomic_load(slot_of(seq), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+
+    const int KT = Main::kBK > 0 ? Kdim / Main::kBK : 0;
+    const int64_t b1_delta = kSwiglu ? B1 - B0 : 0;
+    int cur_t, nxt_t;   // the tile being computed and the next one, as table entries (-1: none)
+    int after_next = -1; // the tile after `nxt`, picked up from the ticket slot inside the K loop
+
+    // ---- everything that depends on the tile geometry.  One call works through the workgroup's
+    //      tiles as long as they are of this geometry's kind.
+    auto engine = [&](auto cfg_tag) {
+    using Cfg = decltype(cfg_tag);
+    constexpr int BM = Cfg::BM, WN = Cfg::WN, kBK = Cfg::kBK, kUnits = Cfg::kUnits;
+    constexpr int kDistA = Cfg::kDistA, kDistB = Cfg::kDistB;
+    constexpr int kChunks = Cfg::kChunks, kRowBytes = Cfg::kRowBytes, kKSteps = Cfg::kKSteps;
+    constexpr int kDepth = Cfg::kDepth, kAheadA = Cfg::kAheadA;
+    const int wm = wave / WN, wn = wave % WN;
 
     // ---- global->LDS loads (buffer_load_dwordx4 ... lds): the lane at 16-byte position p of its
     //      row fetches chunk p ^ key(row).  Buffer addressing keeps the per-lane part of the address
@@ -281,10 +312,10 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
         }
         b_off[g] = (col * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8)) * 2;
     }
-    const int KT = Kdim / kBK;
     // With kDepth + kAheadA K tiles or more per output tile, the loads that would run past the
-    // end of a tile's reduction fetch the first K tiles of the workgroup's next tile, so that tile
-    // starts with its operands in LDS.  (Shorter reductions start every tile from scratch.)
+    // end of a tile's reduction fetch the first K tiles of the workgroup's next tile (if that is
+    // of the same kind), so that tile starts with its operands in LDS.  (Shorter reductions
+    // start every tile from scratch.)
     const bool warm = KT >= kDepth + kAheadA;
 
     // What the loads of a tile need.  Rows past the end of the segment (and columns past Ndim) lie
@@ -297,7 +328,6 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
         uint32_t a_bytes, b_bytes;
         int32_t m0, m_end, n0;
     };
-    const int64_t b1_delta = kSwiglu ? B1 - B0 : 0;
     auto operands_of = [&](int tile) {
         Operands o = {A, B0, 0u, 0u, 0, 0, 0};
         if (tile >= 0) {
@@ -324,7 +354,7 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
         const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint16_t *>(here ? cur.a : nxt.a), 0, here ? cur.a_bytes : nxt.a_bytes, 0x00020000);
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rs, (lds_ptr)(lds + unit * Cfg::kUnitBytes + (wave * Cfg::kAGroups + g) * 1024), 16, a_off[g],
+            rs, (lds_ptr)(lds + Cfg::unit_base(unit) + (wave * Cfg::kAGroups + g) * 1024), 16, a_off[g],
             (here ? t : t - KT) * (kBK * 2), 0, 0);
     };
     auto load_b_group = [&](int t, int unit, int g, auto tail_tag) {
@@ -336,7 +366,7 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
             const_cast<uint16_t *>((here ? cur.b : nxt.b) + (up ? b1_delta : 0)), 0,
             here ? cur.b_bytes : nxt.b_bytes, 0x00020000);
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rs, (lds_ptr)(lds + unit * Cfg::kUnitBytes + (wave * Cfg::kBGroups + g) * 1024), 16, b_off[g],
+            rs, (lds_ptr)(lds + Cfg::unit_base(unit) + (wave * Cfg::kBGroups + g) * 1024), 16, b_off[g],
             (here ? t : t - KT) * (kBK * 2), 0, 0);
     };
 
@@ -385,8 +415,8 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
     // the end of a ragged segment are neither read nor multiplied.
     auto read_frags = [&](int u, int ks, int slot, auto act_tag) { // u = A unit of the tile
         constexpr int kAct = decltype(act_tag)::value;
-        const unsigned char *pa = lds + u * Cfg::kUnitBytes + (a_off0 ^ (ks << 5));
-        const unsigned char *pb = lds + wrap(u + 1) * Cfg::kUnitBytes + (b_off0 ^ (ks << 5));
+        const unsigned char *pa = lds + Cfg::unit_base(u) + (a_off0 ^ (ks << 5));
+        const unsigned char *pb = lds + Cfg::unit_base(wrap(u + 1)) + (b_off0 ^ (ks << 5));
 #pragma unroll
         for (int i = 0; i < kAct; ++i)
             fa[slot][i] = *reinterpret_cast<const bf16x8 *>(pa + i * 32 * kRowBytes);
@@ -407,8 +437,7 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
     };
 
-    int u = 0;      // ring position: A unit of the K tile to multiply next
-    int after_next; // the tile after `nxt`, picked up from the ticket slot inside the K loop
+    int u = 0; // ring position: A unit of the K tile to multiply next
 
     // One output tile: K loop, then the epilogue.  On entry K tile 0 of `cur` is in LDS (everyone's
     // loads, behind a barrier) and the windows before it have issued what they should.
@@ -504,31 +533,13 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
         }
     };
 
-    // ---- the workgroup's first three tiles.  The words still hold what an earlier launch left
-    //      there, so these stores have to be in memory before anyone looks.
-    seq = 1;
-    if (tid == 0) {
-        int t = 0;
-#pragma unroll 1
-        for (int w = 0; w < 3; ++w) {
-            t = t >= 0 ? fetch_tile() : -1;
-            if (w < 2)
-                __hip_atomic_store(my_ticket + w, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            else
-                publish(t);
-        }
-    }
-    MOE_WAIT_VMCNT(0);
-    __syncthreads();
-    int cur_t = __builtin_amdgcn_readfirstlane(
-        __hip_atomic_load(my_ticket + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    int nxt_t = __builtin_amdgcn_readfirstlane(
-        __hip_atomic_load(my_ticket + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     bool primed = false; // K tile 0 of `cur` is in LDS already
-    while (cur_t >= 0) {
+    while (cur_t >= 0 && kind_of(cur_t) == Cfg::kKind) {
+        // the next tile's first K tiles ride behind this one's last
+        const bool chain = warm && nxt_t >= 0 && kind_of(nxt_t) == Cfg::kKind;
+        nxt = operands_of(chain ? nxt_t : -1);
         if (!primed) {
             cur = operands_of(cur_t);
-            nxt = operands_of(warm ? nxt_t : -1);
             // everything the windows before K tile 0 would have issued, then position 0 of the
             // window before it; K tile 0 landed
             u = 0;
@@ -562,10 +573,6 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
         else
             run_tile(std::integral_constant<int, (Cfg::kBlkM > 3 ? 3 : 1)>{});
 
-        if (!warm) {
-            MOE_WAIT_VMCNT(0); // the no-op loads past the last K tile still write LDS: let them finish
-            lds_barrier();     // before anyone refills those units
-        }
         // Thread 0 draws the tile that will follow `after_next` and leaves it in the other slot under
         // the next sequence number; the others look there after the next tile's first barrier.
         ++seq;
@@ -573,10 +580,45 @@ __global__ __launch_bounds__(WM *WN *kWave, (BM * BN <= 256 * 128 ? 2 : 1)) void
             publish(after_next >= 0 ? fetch_tile() : -1);
         cur_t = nxt_t;
         nxt_t = after_next;
-        if (warm) {
+        if (chain) {
             cur = nxt; // its first K tiles are in LDS or on their way
-            nxt = operands_of(nxt_t);
             primed = true;
+        } else {
+            primed = false;
+            MOE_WAIT_VMCNT(0); // the no-op loads past the last K tile still write LDS: let them finish
+            lds_barrier();     // before anyone refills those units, in this layout or the other
+        }
+    }
+    }; // engine
+
+    // ---- the workgroup's first three tiles.  The words still hold what an earlier launch left
+    //      there, so these stores have to be in memory before anyone looks.
+    seq = 1;
+    if (tid == 0) {
+        int t = 0;
+#pragma unroll 1
+        for (int w = 0; w < 3; ++w) {
+            t = t >= 0 ? fetch_tile() : -1;
+            if (w < 2)
+                __hip_atomic_store(my_ticket + w, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else
+                publish(t);
+        }
+    }
+    MOE_WAIT_VMCNT(0);
+    __syncthreads();
+    cur_t = __builtin_amdgcn_readfirstlane(
+        __hip_atomic_load(my_ticket + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    nxt_t = __builtin_amdgcn_readfirstlane(
+        __hip_atomic_load(my_ticket + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    while (cur_t >= 0) {
+        if constexpr (kTwo) {
+            if (kind_of(cur_t) == 1)
+                engine(std::conditional_t<kTwo, Light, Main>{});
+            else
+                engine(Main{});
+        } else {
+            engine(Main{});
         }
     }
     MOE_WAIT_VMCNT(0);
