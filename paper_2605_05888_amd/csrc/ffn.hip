@@ -26,18 +26,10 @@ namespace moe {
 // ------------------------------------------------------------------------
 constexpr int kSchedThreads = 256;
 // relative cost of a tile of a one-row-tile expert and of a full tile, for sharing out the workgroup slots
-#ifndef MOE_LIGHT_COST
-#define MOE_LIGHT_COST 3
-#endif
-constexpr int kLightCost = MOE_LIGHT_COST, kHeavyCost = 7;
-#ifndef MOE_ORDER_BLOCK
-#define MOE_ORDER_BLOCK 4
-#endif
-constexpr int kOrderBlock = MOE_ORDER_BLOCK;
+constexpr int kLightCost = 3, kHeavyCost = 7;
+constexpr int kOrderRows = 4, kOrderCols = 4; // block of the tile order inside an expert
 // experts with at most this many rows go through the shallow tile geometry
-#ifndef MOE_LIGHT_ROWS
-#define MOE_LIGHT_ROWS 64
-#endif
+constexpr int kLightRows = 64;
 
 // Experts come in two classes: "light" ones with at most `light_rows` rows, whose one row tile
 // streams its weights from memory once and mostly waits for them (the GEMM has a shallow, deeply
@@ -138,22 +130,22 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
         int64_t lo;
         const int32_t n_rows_e = clamped_rows(seg_offsets, e, M, lo);
         const int m_tiles = (n_rows_e + BM - 1) / BM;
-        // Inside an expert the tiles go in blocks of kOrderBlock x kOrderBlock (row tiles x column
+        // Inside an expert the tiles go in blocks of kOrderRows x kOrderCols (row tiles x column
         // tiles): the 16 tiles an XCD takes together then share 4 weight tiles and 4 activation
         // tiles in its L2, instead of one and 16.
         const int local = pos - start[c][e];
-        const int band_tiles = kOrderBlock * n_tiles; // tiles of a full band of kOrderBlock row tiles
+        const int band_tiles = kOrderRows * n_tiles; // tiles of a full band of kOrderRows row tiles
         int rb = local / band_tiles;
-        const int last_band = (m_tiles - 1) / kOrderBlock;
+        const int last_band = (m_tiles - 1) / kOrderRows;
         rb = rb > last_band ? last_band : rb;
-        const int h = m_tiles - rb * kOrderBlock < kOrderBlock ? m_tiles - rb * kOrderBlock : kOrderBlock;
+        const int h = m_tiles - rb * kOrderRows < kOrderRows ? m_tiles - rb * kOrderRows : kOrderRows;
         const int in_band = local - rb * band_tiles;
-        const int cb = in_band / (kOrderBlock * h);
-        const int in_block = in_band - cb * kOrderBlock * h;
+        const int cb = in_band / (kOrderCols * h);
+        const int in_block = in_band - cb * kOrderCols * h;
         TileEntry t;
         t.expert = e;
-        t.n_tile = cb * kOrderBlock + in_block / h;
-        t.m0 = (int32_t)lo + (rb * kOrderBlock + in_block % h) * BM;
+        t.n_tile = cb * kOrderCols + in_block / h;
+        t.m0 = (int32_t)lo + (rb * kOrderRows + in_block % h) * BM;
         t.m_end = (int32_t)lo + n_rows_e;
         table[L] = t;
     }
@@ -353,10 +345,10 @@ int launch_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     const FfnPlan p = make_plan(M, H, F, E_local);
     const FfnWorkspace k = carve(p, ws);
     hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(k.max1, kSchedThreads)),
-                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles1, MOE_LIGHT_ROWS, k.max1,
+                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles1, kLightRows, k.max1,
                        k.hdr1, k.tab1);
     hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(k.max2, kSchedThreads)),
-                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles2, MOE_LIGHT_ROWS, k.max2,
+                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles2, kLightRows, k.max2,
                        k.hdr2, k.tab2);
     return check_launch("moe_ffn_schedule");
 }

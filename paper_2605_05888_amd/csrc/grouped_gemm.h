@@ -5,7 +5,7 @@
 // BM x BN tile; every wavefront owns a (BM/WM) x (BN/WN) sub-tile as 32x32 blocks of
 // v_mfma_f32_32x32x16_bf16.
 //
-// Pipeline (K tiles of BK = 32 or 64 elements; LDS is a ring of U units, a unit holding the A rows
+// Pipeline (K tiles of BK = 64 elements; LDS is a ring of U units, a unit holding the A rows
 // or the B rows of one K tile):
 //   * global -> LDS goes through buffer_load_dwordx4 ... lds: no staging registers, no
 //     ds_write.  A wavefront instruction fills 1 KiB of consecutive tile rows; the
@@ -28,6 +28,14 @@
 //   * kSwiglu: the B tile holds BN/2 gate rows and the same BN/2 up rows, arranged
 //     so that each wavefront has matching gate/up blocks; the epilogue writes
 //     silu(g)*u, so g and u never reach memory.
+//
+// Scheduling: the grid is persistent, one workgroup per compute unit.  Workgroups draw tiles
+// from per-XCD counters of the tile table (own XCD first), so the 16 tiles an XCD holds at a
+// time are neighbours in the table's order; while a workgroup multiplies the last K tiles of
+// one output tile, its loads already fetch the first K tiles of its next one.  The table has
+// two streams of tiles, served by two tile geometries inside the one kernel: 256x256 tiles, and
+// 64x256 tiles four K tiles deep for experts with at most 64 rows, which do little arithmetic
+// and live on how many bytes they keep in flight.
 #pragma once
 
 #include <type_traits>
