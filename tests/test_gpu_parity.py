@@ -154,11 +154,16 @@ def _segments(rng, M, E, empty=()):
     return seg
 
 
+# the grouped GEMM has two tile geometries (experts with at most 64 rows, and the rest), draws
+# tiles at run time and carries on from one tile into the next when the reduction has three K
+# tiles of 64 or more: the cases mix expert sizes and put H and F on both sides of that length
 FFN_CASES = [  # M, H, F, E_local, dtype, empty experts
     (300, 128, 192, 5, mi.BF16, (1,)),        # small-tile plan, ragged rows and columns
     (1500, 256, 320, 3, mi.BF16, ()),         # big-tile plan, several row tiles, F not a tile multiple
     (900, 64, 64, 1, mi.BF16, ()),            # one expert
     (130, 192, 448, 40, mi.BF16, (0, 7, 39)), # many tiny experts, some empty
+    (2600, 576, 128, 6, mi.BF16, (2,)),       # long first reduction, short second; big and small experts
+    (700, 64, 640, 9, mi.BF16, ()),           # short first reduction (one K tile), long second
     (512, 128, 256, 8, mi.F32, ()),           # fp32 path
     (77, 36, 20, 3, mi.F32, (1,)),            # fp32, odd sizes
 ]
@@ -178,6 +183,34 @@ def test_grouped_ffn_parity(G, M, H, F, E, dtype, empty):
     y = G.gpu_ffn(mid.to_device(xp), mid.to_device(seg), mid.to_device(Wg), mid.to_device(Wu), mid.to_device(Wd))
     ma, rl = G.check_close(G.host(y), want, *G.tolerances(cfg), what="ffn")
     _say("   max-abs %.3e rel-L2 %.3e" % (ma, rl))
+
+
+def test_ffn_steps_rerun_after_one_schedule(G):
+    """The tile counters are handed back by the GEMM itself: after one moe_ffn_schedule the two
+    GEMM steps can be launched again and again, and moe_grouped_ffn gives the same bits."""
+    import moe_inputs.device as mid
+    import dataclasses
+    import torch
+    import paper_2605_05888_amd as hub
+    cfg = dataclasses.replace(mi.CONFIGS["mixtral"], N=1800, H=320, F=384, E=7, K=1, seed=9)
+    rng = np.random.default_rng(3)
+    seg = _segments(rng, cfg.N, cfg.E, (4,))
+    seg[1] = seg[0] + 20                                    # a 20-row expert next to big ones
+    seg = np.maximum.accumulate(seg)
+    xp = mid.to_device(mi.host_tensor(cfg, mi.STREAM_X))
+    Wg, Wu, Wd = (mid.to_device(mi.host_tensor(cfg, s)) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    dseg = mid.to_device(seg)
+    ref = G.host(G.gpu_ffn(xp, dseg, Wg, Wu, Wd)).tobytes()
+    ws = torch.zeros(hub.workspace_bytes(hub.OP_GROUPED_FFN, N=cfg.N, H=cfg.H, E=cfg.E, F=cfg.F), dtype=torch.uint8,
+                     device="cuda:0")
+    hub.moe_ffn_schedule(hub.BF16, cfg.N, cfg.H, cfg.F, dseg, ws)
+    for _ in range(3):
+        y = torch.zeros((cfg.N, cfg.H), dtype=torch.bfloat16, device="cuda:0")
+        hub.moe_ffn_gate_up(xp, dseg, Wg, Wu, ws)
+        hub.moe_ffn_gate_up(xp, dseg, Wg, Wu, ws)           # twice in a row over the same table
+        hub.moe_ffn_down(dseg, Wd, y, ws)
+        torch.cuda.synchronize()
+        assert G.host(y).tobytes() == ref
 
 
 def test_grouped_ffn_leaves_rows_outside_segments_untouched(G):
