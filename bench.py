@@ -41,10 +41,12 @@ WORKLOAD_TEXT = {
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="mixtral", choices=list(WORKLOAD_TEXT))
     ap.add_argument("--tokens", type=int, default=0, help="override the workload's token count (token-count sweeps)")
+    ap.add_argument("--zipf", type=float, default=-1.0,
+                    help="override the Zipf exponent of expert popularity (imbalance sweeps; 0 = uniform)")
     ap.add_argument("--nbuf", type=int, default=0, help="activation buffer sets rotated per step (0 = auto)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample (0 = skip)")
     return ap.parse_args()
@@ -191,6 +193,9 @@ def main():
     if args.tokens > 0:
         import dataclasses
         cfg = dataclasses.replace(cfg, N=args.tokens)
+    if args.zipf >= 0:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, zipf_s=args.zipf)
     N, H, E, K, F, G = cfg.N, cfg.H, cfg.E, cfg.K, cfg.F, cfg.G
     R, b = N * K, cfg.elt_bytes
     act_bytes = (2 * N * H + 2 * R * H + R * F) * b
@@ -236,6 +241,29 @@ def main():
                              "permute_frac": gbs_perm / PEAK_HBM_GBS, "combine_frac": gbs_comb / PEAK_HBM_GBS},
         "step_breakdown_us": us,
     }
+    # what the routing did: rows per expert, and the paper's imbalance measure (std of the experts' token shares)
+    cnt = layer.sets[0]["cnt"].cpu().numpy().astype("float64")
+    result["config"]["routing"] = {"zipf_s": cfg.zipf_s, "rows_per_expert_min": int(cnt.min()),
+                                   "rows_per_expert_max": int(cnt.max()),
+                                   "std_of_expert_share": float((cnt / max(cnt.sum(), 1.0)).std())}
+    # achievable matrix rate of this box with this kernel: the gate/up GEMM over equal, tile-aligned segments
+    M_even = (R // layer.E_local) // 256 * 256
+    if M_even > 0 and cfg.dtype == mi.BF16:
+        seg_even = (torch.arange(layer.E_local + 1, dtype=torch.int32, device="cuda:0") * M_even).contiguous()
+        s0 = layer.sets[0]
+        src = layer.recv if layer.ep else s0["xp"]
+        rows = M_even * layer.E_local
+        hub.moe_ffn_schedule(layer.code, rows, H, F, seg_even, s0["ffn_ws"])
+        reps = max(3, min(20, int(30e-3 / max(t_gu, 1e-6))))      # about 30 ms of launches, untimed, then the same again
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for timed in (False, True):
+            if timed:
+                g0.record()
+            for _ in range(reps):
+                hub.moe_ffn_gate_up(src[:rows], seg_even, layer.W_gate, layer.W_up, s0["ffn_ws"])
+        g1.record()
+        torch.cuda.synchronize()
+        result["ffn"]["tflops_gate_up_equal_segments"] = reps * 4.0 * rows * H * F / (g0.elapsed_time(g1) * 1e-3) / 1e12
     # achievable copy bandwidth of this machine: plain 1 GiB device-to-device copy (read + write bytes)
     import moe_inputs.device as mid
     src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
