@@ -149,7 +149,10 @@ int moe_grouped_ffn(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
  *   moe_ffn_schedule -> moe_ffn_gate_up -> moe_ffn_down   (in stream order)
  * is exactly moe_grouped_ffn.  moe_ffn_schedule turns seg_offsets into the
  * device-side tile tables both GEMMs read; moe_ffn_gate_up leaves the activation
- * a[M,F] in the workspace; moe_ffn_down reads it and writes y.
+ * a[M,F] in the workspace; moe_ffn_down reads it and writes y.  The GEMM steps
+ * may be launched again over the same schedule.  On a workspace that
+ * moe_ffn_schedule has not filled for the same M (bf16) they find no tile table
+ * and leave their outputs untouched; no error can be reported for that.
  */
 int moe_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
                      const int32_t *seg_offsets, void *ws, size_t ws_bytes, void *stream);

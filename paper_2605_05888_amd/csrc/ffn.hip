@@ -110,6 +110,8 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
         const int64_t wl = (int64_t)len[1] * kLightCost, wh = (int64_t)len[0] * kHeavyCost;
         hdr->light_slots = wl + wh > 0 ? (int32_t)((32 * wl + (wl + wh) / 2) / (wl + wh)) : 0;
         hdr->done = 0;
+        hdr->magic = kTableMagic;
+        hdr->rows = (int32_t)M;
         for (int s = 0; s < 2; ++s)
             for (int x = 0; x < kXcds; ++x)
                 hdr->next[s][x] = 0;

@@ -213,6 +213,30 @@ def test_ffn_steps_rerun_after_one_schedule(G):
         assert G.host(y).tobytes() == ref
 
 
+def test_ffn_gemm_without_schedule_does_nothing(G):
+    """A workspace no schedule was built in holds no tile table: the GEMM steps leave their outputs alone."""
+    import moe_inputs.device as mid
+    import dataclasses
+    import torch
+    import paper_2605_05888_amd as hub
+    cfg = dataclasses.replace(mi.CONFIGS["mixtral"], N=300, H=128, F=128, E=2, K=1, seed=5)
+    xp = mid.to_device(mi.host_tensor(cfg, mi.STREAM_X))
+    Wg, Wu, Wd = (mid.to_device(mi.host_tensor(cfg, s)) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    seg = mid.to_device(np.array([0, 100, 300], np.int32))
+    ws = torch.zeros(hub.workspace_bytes(hub.OP_GROUPED_FFN, N=cfg.N, H=cfg.H, E=cfg.E, F=cfg.F), dtype=torch.uint8,
+                     device="cuda:0")
+    y = torch.full((cfg.N, cfg.H), 3.0, dtype=torch.bfloat16, device="cuda:0")
+    hub.moe_ffn_gate_up(xp, seg, Wg, Wu, ws)
+    hub.moe_ffn_down(seg, Wd, y, ws)
+    torch.cuda.synchronize()
+    assert not ws.any() and bool((y == 3.0).all())
+    hub.moe_ffn_schedule(hub.BF16, cfg.N - 44, cfg.H, cfg.F, seg, ws)     # a schedule for another row count
+    hub.moe_ffn_gate_up(xp, seg, Wg, Wu, ws)
+    hub.moe_ffn_down(seg, Wd, y, ws)
+    torch.cuda.synchronize()
+    assert bool((y == 3.0).all())
+
+
 def test_grouped_ffn_leaves_rows_outside_segments_untouched(G):
     import moe_inputs.device as mid
     import dataclasses
