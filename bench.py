@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--tokens", type=int, default=0, help="override the workload's token count (token-count sweeps)")
     ap.add_argument("--zipf", type=float, default=-1.0,
                     help="override the Zipf exponent of expert popularity (imbalance sweeps; 0 = uniform)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a HIP graph (one graph of all buffer sets' steps)")
     ap.add_argument("--nbuf", type=int, default=0, help="activation buffer sets rotated per step (0 = auto)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample (0 = skip)")
     return ap.parse_args()
@@ -241,6 +243,37 @@ def main():
                              "permute_frac": gbs_perm / PEAK_HBM_GBS, "combine_frac": gbs_comb / PEAK_HBM_GBS},
         "step_breakdown_us": us,
     }
+    if args.graph:
+        # The same steps captured once and replayed: what a serving loop would do with a launch-bound layer.
+        # Every replay is checked against the eager result (the kernels are deterministic, so bit for bit).
+        eager_out = [st["out"].clone() for st in layer.sets]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            for i in range(len(layer.sets)):
+                layer.step(i)                      # warm every buffer set on the capture stream
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(len(layer.sets)):
+                    layer.step(i)
+        torch.cuda.current_stream().wait_stream(side)
+        reps = max(1, args.steps // len(layer.sets))
+        same = True
+        for rnd in range(3):                       # replays with eager work and synchronisation in between
+            for st in layer.sets:
+                st["out"].zero_()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                graph.replay()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            same = same and all(torch.equal(st["out"], e) for st, e in zip(layer.sets, eager_out))
+            layer.step(0)
+        g_ms = (t1 - t0) * 1e3 / (reps * len(layer.sets))
+        result["graph"] = {"ms_per_step": g_ms, "tokens_per_s": N / (g_ms * 1e-3), "steps_per_graph": len(layer.sets),
+                           "replays_timed": reps, "matches_eager_bitwise": bool(same)}
     # what the routing did: rows per expert, and the paper's imbalance measure (std of the experts' token shares)
     cnt = layer.sets[0]["cnt"].cpu().numpy().astype("float64")
     result["config"]["routing"] = {"zipf_s": cfg.zipf_s, "rows_per_expert_min": int(cnt.min()),
