@@ -105,7 +105,9 @@ class Layer:
             self.recv_seg = mid.to_device(seg)
         self.names = ["route", "layout", "permute", "ffn_schedule", "ffn_gate_up", "ffn_down", "combine"]
 
-    def step(self, i, events=None):
+    def step(self, i, events=None, fused_gather=False):
+        """One pass of the layer.  fused_gather (single-device layers only): no permute; the gate/up GEMM
+        fetches its rows from x through row_of_slot."""
         hub, cfg = self.hub, self.cfg
         s = self.sets[i % len(self.sets)]
         rec = (lambda j: events[j].record()) if events is not None else (lambda j: None)
@@ -115,7 +117,8 @@ class Layer:
         hub.moe_dispatch_layout(s["idx"], cfg.E, cfg.G, s["cnt"], s["off"], s["dcnt"], s["doff"], s["slot"],
                                 s["row"], self.layout_ws)
         rec(2)
-        hub.moe_permute(s["x"], cfg.K, s["slot"], s["row"], s["xp"])
+        if not fused_gather:
+            hub.moe_permute(s["x"], cfg.K, s["slot"], s["row"], s["xp"])
         rec(3)
         if self.ep:
             ffn_in, seg = self.recv, self.recv_seg
@@ -123,7 +126,10 @@ class Layer:
             ffn_in, seg = s["xp"], s["off"]
         hub.moe_ffn_schedule(self.code, self.R, cfg.H, cfg.F, seg, s["ffn_ws"])
         rec(4)
-        hub.moe_ffn_gate_up(ffn_in, seg, self.W_gate, self.W_up, s["ffn_ws"])
+        if fused_gather:
+            hub.moe_ffn_gate_up_gather(s["x"], cfg.K, seg, s["row"], self.W_gate, self.W_up, s["ffn_ws"])
+        else:
+            hub.moe_ffn_gate_up(ffn_in, seg, self.W_gate, self.W_up, s["ffn_ws"])
         rec(5)
         hub.moe_ffn_down(seg, self.W_down, s["y"], s["ffn_ws"])
         rec(6)
@@ -243,6 +249,21 @@ def main():
                              "permute_frac": gbs_perm / PEAK_HBM_GBS, "combine_frac": gbs_comb / PEAK_HBM_GBS},
         "step_breakdown_us": us,
     }
+    if not layer.ep:
+        # Variant without a dispatch row move (a single device that computes every expert needs no send
+        # buffer): the gate/up GEMM gathers its rows from x.  Reported beside the layer, not as `value`.
+        for i in range(min(3, args.warmup)):
+            layer.step(i, fused_gather=True)
+        evf = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            layer.step(i, evf[i], fused_gather=True)
+        torch.cuda.synchronize()
+        f_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        f_gu = sum(e[4].elapsed_time(e[5]) for e in evf) * 1e3 / args.steps
+        result["fused_gather"] = {"ms_per_step": f_ms, "tokens_per_s": N / (f_ms * 1e-3), "gate_up_us": f_gu,
+                                  "tflops_gate_up": flops_gu / (f_gu * 1e-6) / 1e12}
     if args.graph:
         # The same steps captured once and replayed: what a serving loop would do with a launch-bound layer.
         # Every replay is checked against the eager result (the kernels are deterministic, so bit for bit).

@@ -160,6 +160,23 @@ int moe_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
                     int E_local, const int32_t *seg_offsets,
                     const void *W_gate, const void *W_up,
                     void *ws, size_t ws_bytes, void *stream);
+/*
+ * GEMM1 with the dispatch's row move folded into its operand loads: the paper's
+ * ideal layer has no data-shuffling step between gating and the experts (Section
+ * III-A; the "extra data manipulations" of Section VI-B are what it removes).  Row
+ * m of the virtual xp is x[row_of_slot[m] / K, :], fetched where moe_ffn_gate_up
+ * would fetch xp[m, :]; xp is neither written nor read.  The result, a[N*K,F] in
+ * the workspace, is bit for bit that of moe_permute followed by moe_ffn_gate_up,
+ * and moe_ffn_schedule (with M = N*K) / moe_ffn_down go before / after it as
+ * they do there.  For a single device that computes all experts itself; an
+ * expert-parallel rank still needs the materialised send buffer.
+ *   x [N,H] dtype    row_of_slot [N*K] int32 (of moe_dispatch_layout)
+ * bf16 needs N*H*2 bytes of x to stay below 4 GiB (MOE_ERR_UNSUPPORTED otherwise).
+ */
+int moe_ffn_gate_up_gather(const void *x, int dtype, int64_t N, int K, int64_t H, int64_t F,
+                           int E_local, const int32_t *seg_offsets, const int32_t *row_of_slot,
+                           const void *W_gate, const void *W_up,
+                           void *ws, size_t ws_bytes, void *stream);
 int moe_ffn_down(int dtype, int64_t M, int64_t H, int64_t F,
                  int E_local, const int32_t *seg_offsets, const void *W_down,
                  void *y, void *ws, size_t ws_bytes, void *stream);

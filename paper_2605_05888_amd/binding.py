@@ -30,6 +30,8 @@ _SIGNATURES = {
     "moe_ffn_schedule": (_c_int, [_c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_sz, _c_vp]),
     "moe_ffn_gate_up": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp,
                                  _c_vp, _c_sz, _c_vp]),
+    "moe_ffn_gate_up_gather": (_c_int, [_c_vp, _c_int, _c_i64, _c_int, _c_i64, _c_i64, _c_int, _c_vp, _c_vp,
+                                        _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
     "moe_ffn_down": (_c_int, [_c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
     "moe_combine": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp, _c_vp]),
 }
@@ -181,6 +183,20 @@ def moe_ffn_gate_up(xp, seg_offsets, W_gate, W_up, ws):
     wp, wb = _ws_args(ws)
     _check(load_library().moe_ffn_gate_up(_ptr(xp), _dtype_code(xp), M, H, F, E_local, _ptr(seg_offsets),
                                           _ptr(W_gate), _ptr(W_up), wp, wb, _stream()))
+
+
+def moe_ffn_gate_up_gather(x, K: int, seg_offsets, row_of_slot, W_gate, W_up, ws):
+    import torch
+    N, H = x.shape
+    E_local, F, _ = W_gate.shape
+    assert tuple(W_up.shape) == tuple(W_gate.shape) and W_gate.shape[2] == H
+    assert x.is_contiguous() and W_gate.is_contiguous() and W_up.is_contiguous()
+    assert seg_offsets.numel() == E_local + 1
+    _need(row_of_slot, torch.int32, "row_of_slot")
+    assert row_of_slot.numel() == N * K
+    wp, wb = _ws_args(ws)
+    _check(load_library().moe_ffn_gate_up_gather(_ptr(x), _dtype_code(x), N, K, H, F, E_local, _ptr(seg_offsets),
+                                                 _ptr(row_of_slot), _ptr(W_gate), _ptr(W_up), wp, wb, _stream()))
 
 
 def moe_ffn_down(seg_offsets, W_down, y, ws):

@@ -241,6 +241,31 @@ extern "C" int moe_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, 
                               static_cast<hipStream_t>(stream));
 }
 
+extern "C" int moe_ffn_gate_up_gather(const void *x, int dtype, int64_t N, int K, int64_t H, int64_t F,
+                                      int E_local, const int32_t *seg_offsets,
+                                      const int32_t *row_of_slot, const void *W_gate,
+                                      const void *W_up, void *ws, size_t ws_bytes, void *stream)
+{
+    clear_error();
+    if (N < 0 || K < 1 || N * (int64_t)K >= ((int64_t)1 << 31))
+        return fail(MOE_ERR_ARG, "need N >= 0, K >= 1, N*K < 2^31 (got N=%lld, K=%d)", (long long)N, K);
+    const int64_t M = N * K;
+    MOE_TRY(check_ffn_common(dtype, M, H, F, E_local, seg_offsets, ws, ws_bytes));
+    if (M == 0)
+        return MOE_OK;
+    // the gathered rows are addressed with 32-bit byte offsets from x
+    if (dtype == MOE_BF16 && (N + 1) * H * 2 + 4096 >= ((int64_t)1 << 32))
+        return fail(MOE_ERR_UNSUPPORTED, "moe_ffn_gate_up_gather needs x below 4 GiB (got N=%lld, H=%lld)",
+                    (long long)N, (long long)H);
+    MOE_NEED(x);
+    MOE_NEED(W_gate);
+    MOE_NEED(W_up);
+    if (!row_of_slot)
+        return fail(MOE_ERR_ARG, "row_of_slot must not be NULL");
+    return launch_ffn_gate_up(x, dtype, M, H, F, E_local, seg_offsets, W_gate, W_up, ws,
+                              static_cast<hipStream_t>(stream), row_of_slot, K, N);
+}
+
 extern "C" int moe_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
                             const int32_t *seg_offsets, const void *W_down, void *y, void *ws,
                             size_t ws_bytes, void *stream)

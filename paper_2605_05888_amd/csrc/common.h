@@ -70,7 +70,7 @@ int launch_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
                         const int32_t *seg_offsets, void *ws, hipStream_t st);
 int launch_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t F, int E_local,
                        const int32_t *seg_offsets, const void *W_gate, const void *W_up, void *ws,
-                       hipStream_t st);
+                       hipStream_t st, const int32_t *gather_rows = nullptr, int K = 1, int64_t N = 0);
 int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
                     const int32_t *seg_offsets, const void *W_down, void *y, void *ws,
                     hipStream_t st);

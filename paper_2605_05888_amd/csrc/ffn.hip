@@ -172,12 +172,14 @@ __device__ __forceinline__ int expert_of_row(const int32_t *seg, int E_local, in
     return (m >= seg[lo] && m < seg[lo + 1]) ? lo : -1;
 }
 
+// gather_rows != nullptr: row m of xp is row gather_rows[m] / gather_div of `xp`
 __global__ __launch_bounds__(256) void ffn_f32_gate_up(const float *__restrict__ xp, int64_t M, int H,
                                                      int F, int E_local,
                                                      const int32_t *__restrict__ seg,
                                                      const float *__restrict__ Wg,
                                                      const float *__restrict__ Wu,
-                                                     float *__restrict__ a)
+                                                     float *__restrict__ a,
+                                                     const int32_t *__restrict__ gather_rows, int gather_div)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= M * F)
@@ -187,7 +189,7 @@ __global__ __launch_bounds__(256) void ffn_f32_gate_up(const float *__restrict__
     const int e = expert_of_row(seg, E_local, m);
     if (e < 0)
         return;
-    const float *xr = xp + m * H;
+    const float *xr = xp + (gather_rows ? (int64_t)(gather_rows[m] / gather_div) : m) * H;
     const float *g = Wg + ((int64_t)e * F + f) * H;
     const float *u = Wu + ((int64_t)e * F + f) * H;
     float sg = 0.0f, su = 0.0f;
@@ -284,12 +286,13 @@ static int workgroup_slots(int per_cu)
     return g < kXcds ? kXcds : g;
 }
 
-template <class Main, class Light, bool kSwiglu>
+template <class Main, class Light, bool kSwiglu, bool kGather = false>
 static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const uint16_t *B0,
                         const uint16_t *B1, uint16_t *C, TileTableHeader *hdr,
-                        const TileEntry *table, int patch, hipStream_t st)
+                        const TileEntry *table, int patch, hipStream_t st,
+                        const int32_t *gather_rows = nullptr, int gather_div = 1, uint32_t gather_bytes = 0)
 {
-    auto kern = grouped_gemm_bf16<Main, Light, kSwiglu>;
+    auto kern = grouped_gemm_bf16<Main, Light, kSwiglu, kGather>;
     size_t lds_bytes = Main::kLdsBytes;
     if constexpr (!std::is_void<Light>::value)
         lds_bytes = lds_bytes > Light::kLdsBytes ? lds_bytes : Light::kLdsBytes;
@@ -302,7 +305,7 @@ static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const 
     // persistent grid: the workgroups draw their tiles from the table's counters
     const int grid = workgroup_slots(Main::kLdsBytes <= 80 * 1024 ? 2 : 1);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(Main::kThreads), lds_bytes, st, A, M, Kdim, Ndim, B0, B1, C,
-                       hdr, table, patch);
+                       hdr, table, patch, gather_rows, gather_div, gather_bytes);
 }
 
 int check_ffn_shape(int dtype, int64_t H, int64_t F)
@@ -355,22 +358,27 @@ int launch_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     return check_launch("moe_ffn_schedule");
 }
 
+// gather_rows == nullptr: xp holds the M rows.  Otherwise xp is x[N, H] and row m is x[gather_rows[m] / K].
 int launch_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t F, int E_local,
                        const int32_t *seg_offsets, const void *W_gate, const void *W_up, void *ws,
-                       hipStream_t st)
+                       hipStream_t st, const int32_t *gather_rows, int K, int64_t N)
 {
     if (dtype == MOE_F32) {
         hipLaunchKernelGGL(ffn_f32_gate_up, dim3((unsigned)ceil_div(M * F, 256)), dim3(256), 0, st,
                            static_cast<const float *>(xp), M, (int)H, (int)F, E_local, seg_offsets,
                            static_cast<const float *>(W_gate), static_cast<const float *>(W_up),
-                           static_cast<float *>(ws));
+                           static_cast<float *>(ws), gather_rows, K);
         return check_launch("moe_ffn_gate_up(f32)");
     }
     const FfnPlan p = make_plan(M, H, F, E_local);
     const FfnWorkspace k = carve(p, ws);
     const uint16_t *xpb = static_cast<const uint16_t *>(xp);
     const uint16_t *wg = static_cast<const uint16_t *>(W_gate), *wu = static_cast<const uint16_t *>(W_up);
-    launch_gemm<BigTile<true>, ShallowTile<true>, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, kPatch, st);
+    if (gather_rows)
+        launch_gemm<BigTile<true>, ShallowTile<true>, true, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1,
+                                                                  kPatch, st, gather_rows, K, (uint32_t)(N * H * 2));
+    else
+        launch_gemm<BigTile<true>, ShallowTile<true>, true>(xpb, M, (int)H, (int)F, wg, wu, k.a, k.hdr1, k.tab1, kPatch, st);
     return check_launch("moe_ffn_gate_up");
 }
 

@@ -217,12 +217,15 @@ struct GemmCfg {
 // Persistent grouped GEMM.  Main: the geometry of stream 0 (and of everything when there is no
 // second geometry); Light: the geometry of stream 1, tiles of experts with at most Light::BM rows,
 // or `void`.  Both geometries have the same workgroup size, BN and K tile.
-template <class Main, class Light, bool kSwiglu>
+// kGather: row m of the A operand is row gather_rows[m] / gather_div of `A` (the dispatch's row
+// move done by the operand loads themselves) instead of row m.
+template <class Main, class Light, bool kSwiglu, bool kGather>
 __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 : 1)) void grouped_gemm_bf16(
     const uint16_t *__restrict__ A, int64_t M, int Kdim, int Ndim,
     const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
     uint16_t *__restrict__ C, TileTableHeader *__restrict__ hdr,
-    const TileEntry *__restrict__ table, int patch)
+    const TileEntry *__restrict__ table, int patch,
+    const int32_t *__restrict__ gather_rows, int gather_div, uint32_t gather_bytes)
 {
 #if defined(__HIP_DEVICE_COMPILE__) // the body uses device-only types (buffer resources); the host pass only needs the stub
     constexpr bool kTwo = !std::is_void<Light>::value;
@@ -304,11 +307,15 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
     //      in one 32-bit register (row offset inside the tile, the same for every tile and the whole
     //      K loop); the tile base sits in the scalar resource and the K offset in a scalar register.
     const int ld_row = lane / kChunks, ld_pc = lane % kChunks;
+    // (kGather: the row part of the offset differs from tile to tile and is looked up, a_off holds
+    // the chunk part; cur_row / nxt_row hold the row parts of `cur` and `nxt`)
     int a_off[Cfg::kAGroups];
+    uint32_t cur_row[Cfg::kAGroups], nxt_row[Cfg::kAGroups];
 #pragma unroll
     for (int g = 0; g < Cfg::kAGroups; ++g) {
         const int r = (wave * Cfg::kAGroups + g) * Cfg::kGroupRows + ld_row;
-        a_off[g] = (r * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8)) * 2;
+        a_off[g] = ((kGather ? 0 : r * Kdim) + ((ld_pc ^ row_key<kChunks>(r)) * 8)) * 2;
+        cur_row[g] = nxt_row[g] = 0u;
     }
     // B rows of one wavefront (kSwiglu): first half gate columns, second half the same up columns.
     // A load group never straddles the two halves, so its resource is wave-uniform.
@@ -348,8 +355,13 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
             const int n0 = te.n_tile * Cfg::kOutCols;
             const int64_t rows_left = (int64_t)te.m_end - te.m0; // >= 1
             const int cols_left = Ndim - n0;                      // >= 1
-            o.a = A + (int64_t)te.m0 * Kdim;
-            o.a_bytes = (uint32_t)((rows_left < BM ? rows_left : BM) * (int64_t)Kdim * 2);
+            if (kGather) { // any row of A may be needed; rows past the segment get an offset past the end
+                o.a = A;
+                o.a_bytes = gather_bytes;
+            } else {
+                o.a = A + (int64_t)te.m0 * Kdim;
+                o.a_bytes = (uint32_t)((rows_left < BM ? rows_left : BM) * (int64_t)Kdim * 2);
+            }
             o.b = B0 + ((int64_t)te.expert * Ndim + n0) * Kdim;
             o.b_bytes = (uint32_t)((cols_left < Cfg::kOutCols ? cols_left : Cfg::kOutCols) * (int64_t)Kdim * 2);
             o.m0 = te.m0;
@@ -359,6 +371,21 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         return o;
     };
     Operands cur, nxt; // the tile being computed; the one whose first K tiles are fetched behind it
+    // kGather: the lane's rows of a tile -> their entries of gather_rows (rows past the segment: ~0) ...
+    auto gather_lookup = [&](const Operands &o, uint32_t (&row)[Cfg::kAGroups]) {
+#pragma unroll
+        for (int g = 0; g < Cfg::kAGroups; ++g) {
+            const int64_t m = (int64_t)o.m0 + (wave * Cfg::kAGroups + g) * Cfg::kGroupRows + ld_row;
+            row[g] = m < o.m_end ? (uint32_t)gather_rows[m] : ~0u;
+        }
+    };
+    // ... -> in place, byte offsets of those rows in A (rows past the segment: just past the last byte,
+    // which the bounds check turns into zeros)
+    auto gather_offsets = [&](uint32_t (&row)[Cfg::kAGroups]) {
+#pragma unroll
+        for (int g = 0; g < Cfg::kAGroups; ++g)
+            row[g] = row[g] != ~0u ? row[g] / (uint32_t)gather_div * (uint32_t)(Kdim * 2) : gather_bytes;
+    };
     using lds_ptr = __attribute__((address_space(3))) void *;
     // K tile t of `cur`; past its last K tile (kTail only): K tile t - KT of `nxt`
     auto load_a_group = [&](int t, int unit, int g, auto tail_tag) {
@@ -367,7 +394,8 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint16_t *>(here ? cur.a : nxt.a), 0, here ? cur.a_bytes : nxt.a_bytes, 0x00020000);
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rs, (lds_ptr)(lds + Cfg::unit_base(unit) + (wave * Cfg::kAGroups + g) * 1024), 16, a_off[g],
+            rs, (lds_ptr)(lds + Cfg::unit_base(unit) + (wave * Cfg::kAGroups + g) * 1024), 16,
+            kGather ? (int)((here ? cur_row[g] : nxt_row[g]) + (uint32_t)a_off[g]) : a_off[g],
             (here ? t : t - KT) * (kBK * 2), 0, 0);
     };
     auto load_b_group = [&](int t, int unit, int g, auto tail_tag) {
@@ -502,6 +530,8 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         // The tile after `nxt`: thread 0 stored it before it reached the barrier of K tile 0.  The
         // load is left in flight and looked at after the K loop.
         uint64_t slot_v = read_slot();
+        if constexpr (kGather)
+            gather_offsets(nxt_row); // looked up before K tile 0, long landed; needed from k_split on
         for (int kt = 1; kt < k_split; ++kt)
             ktile(kt, tail_no{});
         for (int kt = (k_split > 1 ? k_split : 1); kt < KT; ++kt)
@@ -551,8 +581,14 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         // the next tile's first K tiles ride behind this one's last
         const bool chain = warm && nxt_t >= 0 && kind_of(nxt_t) == Cfg::kKind;
         nxt = operands_of(chain ? nxt_t : -1);
+        if constexpr (kGather)
+            gather_lookup(nxt, nxt_row);
         if (!primed) {
             cur = operands_of(cur_t);
+            if constexpr (kGather) {
+                gather_lookup(cur, cur_row);
+                gather_offsets(cur_row);
+            }
             // everything the windows before K tile 0 would have issued, then position 0 of the
             // window before it; K tile 0 landed
             u = 0;
@@ -595,6 +631,11 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         nxt_t = after_next;
         if (chain) {
             cur = nxt; // its first K tiles are in LDS or on their way
+            if constexpr (kGather) {
+#pragma unroll
+                for (int g = 0; g < Cfg::kAGroups; ++g)
+                    cur_row[g] = nxt_row[g];
+            }
             primed = true;
         } else {
             primed = false;

@@ -21,7 +21,7 @@ def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert set(names) == {"moe_last_error", "moe_workspace_bytes", "moe_route", "moe_dispatch_layout",
                           "moe_permute", "moe_grouped_ffn", "moe_combine",
-                          "moe_ffn_schedule", "moe_ffn_gate_up", "moe_ffn_down"}
+                          "moe_ffn_schedule", "moe_ffn_gate_up", "moe_ffn_gate_up_gather", "moe_ffn_down"}
     lib = ctypes.CDLL(hub.lib_path()) if os.path.exists(hub.lib_path()) else hub.load_library()
     for n in names:
         assert hasattr(lib, n), n

@@ -213,6 +213,46 @@ def test_ffn_steps_rerun_after_one_schedule(G):
         assert G.host(y).tobytes() == ref
 
 
+@pytest.mark.parametrize("name", list(SMALL))
+def test_gate_up_with_fused_gather_equals_permute_then_gate_up(G, name):
+    """GEMM1 fetching its rows through row_of_slot from x gives the bits of permute + GEMM1; the whole
+    chain built on it stays within the oracle's tolerance."""
+    import moe_inputs.device as mid
+    import torch
+    import paper_2605_05888_amd as hub
+    cfg = SMALL[name]
+    _say("fused gather", cfg)
+    dt = torch.bfloat16 if cfg.dtype == mi.BF16 else torch.float32
+    code = hub.BF16 if cfg.dtype == mi.BF16 else hub.F32
+    x, Wr = mi.host_tensor(cfg, mi.STREAM_X), mi.host_tensor(cfg, mi.STREAM_W_ROUTER)
+    Wg, Wu, Wd = (mi.host_tensor(cfg, s) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    bias = mi.router_bias(cfg)
+    dx, dWg, dWu, dWd = mid.to_device(x), mid.to_device(Wg), mid.to_device(Wu), mid.to_device(Wd)
+    idx, w, _ = G.gpu_route(dx, mid.to_device(Wr), None if bias is None else mid.to_device(bias), cfg.K,
+                            cfg.score_mode, want_logits=False)
+    lay = G.gpu_layout(idx, cfg.E, cfg.G)
+    seg = lay["expert_offsets"]
+    R = cfg.N * cfg.K
+    nb = hub.workspace_bytes(hub.OP_GROUPED_FFN, N=R, H=cfg.H, E=cfg.E, F=cfg.F, dtype=code)
+    ys = []
+    for fused in (False, True):
+        ws = torch.zeros(nb, dtype=torch.uint8, device="cuda:0")
+        y = torch.zeros((R, cfg.H), dtype=dt, device="cuda:0")
+        hub.moe_ffn_schedule(code, R, cfg.H, cfg.F, seg, ws)
+        if fused:
+            hub.moe_ffn_gate_up_gather(dx.view(dt) if dx.dtype != dt else dx, cfg.K, seg, lay["row_of_slot"], dWg, dWu, ws)
+        else:
+            hub.moe_ffn_gate_up(G.gpu_permute(dx, cfg.K, lay), seg, dWg, dWu, ws)
+        hub.moe_ffn_down(seg, dWd, y, ws)
+        torch.cuda.synchronize()
+        ys.append(G.host(y))
+    assert ys[0].tobytes() == ys[1].tobytes()
+    o_idx, o_w, _ = oracle.route(x, Wr, bias, cfg.K, cfg.score_mode)
+    o_lay = oracle.layout(o_idx, cfg.E, cfg.G)
+    o_y = oracle.ffn_rows(oracle.permute(x, cfg.K, o_lay["slot_of_row"]), o_lay["expert_offsets"], Wg, Wu, Wd)
+    G.check_close(ys[1], o_y, *G.tolerances(cfg), what="y (fused gather)")
+
+
 def test_ffn_gemm_without_schedule_does_nothing(G):
     """A workspace no schedule was built in holds no tile table: the GEMM steps leave their outputs alone."""
     import moe_inputs.device as mid
