@@ -161,6 +161,34 @@ def test_full_ffn_and_combine_on_samples(G, S):
     _say(f"   out max-abs {ma:.3e} rel-L2 {rl:.3e}")
 
 
+def test_full_gate_up_with_fused_gather_is_bit_identical(G, S):
+    """At full size: GEMM1 fetching its rows from x through row_of_slot leaves the same activation in
+    the workspace as GEMM1 over the materialised xp (whose sampled rows the test above checks)."""
+    import torch
+    import paper_2605_05888_amd as hub
+    s = S
+    cfg = s["cfg"]
+    if cfg.G != 1:
+        pytest.skip("an expert-parallel rank computes received rows, not its own")
+    M, H = s["xp"].shape
+    seg = s["lay"]["expert_offsets"]
+    nb = hub.workspace_bytes(hub.OP_GROUPED_FFN, N=M, H=H, E=cfg.E, F=cfg.F, dtype=hub.BF16)
+    a_bytes = M * cfg.F * 2
+    got = []
+    for fused in (False, True):
+        ws = G.ws_tensor(nb)
+        hub.moe_ffn_schedule(hub.BF16, M, H, cfg.F, seg, ws)
+        if fused:
+            hub.moe_ffn_gate_up_gather(s["x"], cfg.K, seg, s["lay"]["row_of_slot"], s["W"][0], s["W"][1], ws)
+        else:
+            hub.moe_ffn_gate_up(s["xp"], seg, s["W"][0], s["W"][1], ws)
+        torch.cuda.synchronize()
+        got.append(ws[:a_bytes].clone())
+        del ws
+    assert torch.equal(got[0], got[1])
+    assert bool(got[0].any())
+
+
 def test_full_combine_of_identity_experts_returns_input(G, S):
     """Holds at any size: with y = xp the weighted sum gives back x (weights sum to one)."""
     s = S

@@ -164,6 +164,7 @@ FFN_CASES = [  # M, H, F, E_local, dtype, empty experts
     (130, 192, 448, 40, mi.BF16, (0, 7, 39)), # many tiny experts, some empty
     (2600, 576, 128, 6, mi.BF16, (2,)),       # long first reduction, short second; big and small experts
     (700, 64, 640, 9, mi.BF16, ()),           # short first reduction (one K tile), long second
+    (3000, 128, 64, 1024, mi.BF16, tuple(range(5, 1024, 7))),  # the largest expert count the schedule takes
     (512, 128, 256, 8, mi.F32, ()),           # fp32 path
     (77, 36, 20, 3, mi.F32, (1,)),            # fp32, odd sizes
 ]
