@@ -406,9 +406,11 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint16_t *>((here ? cur.b : nxt.b) + (up ? b1_delta : 0)), 0,
             here ? cur.b_bytes : nxt.b_bytes, 0x00020000);
+        // The weights of a light tile are read once by one workgroup: fetched with the non-temporal
+        // hint (aux bit 1) they do not push the other tiles' shared operands out of the caches.
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             rs, (lds_ptr)(lds + Cfg::unit_base(unit) + (wave * Cfg::kBGroups + g) * 1024), 16, b_off[g],
-            (here ? t : t - KT) * (kBK * 2), 0, 0);
+            (here ? t : t - KT) * (kBK * 2), 0, Cfg::kKind == 1 ? 2 : 0);
     };
 
     // ---- the ring.  K tile t keeps its A rows in unit (2t) % kUnits and its B rows in unit
