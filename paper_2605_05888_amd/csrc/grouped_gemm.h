@@ -102,21 +102,6 @@ __device__ __forceinline__ int row_key(int r)
 // s_waitcnt lgkmcnt(0) only
 #define MOE_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
 
-// Waits until at most `tiles` K tiles (kLoads loads each) of this lane are still in flight;
-// `tiles` is clamped to [0, kMax].
-template <int kLoads, int kMax>
-__device__ __forceinline__ void wait_tiles_in_flight(int tiles)
-{
-    if constexpr (kMax <= 0) {
-        MOE_WAIT_VMCNT(0);
-    } else {
-        if (tiles >= kMax)
-            MOE_WAIT_VMCNT(kMax * kLoads);
-        else
-            wait_tiles_in_flight<kLoads, kMax - 1>(tiles);
-    }
-}
-
 // Workgroup barrier without the memory fence of __syncthreads (a fence would drain the
 // outstanding global->LDS loads of the tiles still in flight).  The empty asm statements keep
 // the compiler from moving LDS accesses across it.
