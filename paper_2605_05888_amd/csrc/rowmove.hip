@@ -6,6 +6,8 @@
 //             algorithmic bytes = N*H*b (read) + N*K*H*b (write) + 4*N*K (slots)
 //   combine : K rows are gathered per token, scaled, summed in fp32 (k ascending)
 //             and rounded once.  bytes = N*K*H*b (read) + N*H*b (write) + 8*N*K
+#include <type_traits>
+
 #include "common.h"
 
 namespace moe {
@@ -56,38 +58,58 @@ __global__ __launch_bounds__(kWave *kTokensPerBlock) void combine_rows(
         return;
     int32_t my_slot = (lane < K) ? slot_of_row[n * K + lane] : 0;
     float my_w = (lane < K) ? topk_w[n * K + lane] : 0.0f;
-    for (int c = lane; c < chunks; c += kWave) {
-        float acc[8];
+    // kU chunks of a row at a time, so that kU gathers per lane are in flight (a single one leaves
+    // the small workloads, with only a few thousand wavefronts, waiting on memory latency)
+    auto rows_of = [&](auto u_tag, int c) {
+        constexpr int kU = decltype(u_tag)::value;
+        float acc[kU][8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            acc[i] = 0.0f;
-        for (int k = 0; k < K; ++k) {
+        for (int u = 0; u < kU; ++u)
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                acc[u][i] = 0.0f;
+        for (int k = 0; k < K; ++k) { // ascending k: the order of the sum is part of the contract
             const float w = __shfl(my_w, k);
-            const u32x4 v = y[(int64_t)__shfl(my_slot, k) * chunks + c];
+            const u32x4 *src = y + (int64_t)__shfl(my_slot, k) * chunks + c;
+            u32x4 v[kU];
+#pragma unroll
+            for (int u = 0; u < kU; ++u)
+                v[u] = src[u * kWave];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                if (kBf16) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        acc[u][2 * i] = fmaf(w, bf16_bits_to_f32(v[u][i] & 0xFFFFu), acc[u][2 * i]);
+                        acc[u][2 * i + 1] = fmaf(w, __uint_as_float(v[u][i] & 0xFFFF0000u), acc[u][2 * i + 1]);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        acc[u][i] = fmaf(w, __uint_as_float(v[u][i]), acc[u][i]);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            u32x4 o;
             if (kBf16) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    acc[2 * i] = fmaf(w, bf16_bits_to_f32(v[i] & 0xFFFFu), acc[2 * i]);
-                    acc[2 * i + 1] = fmaf(w, __uint_as_float(v[i] & 0xFFFF0000u), acc[2 * i + 1]);
-                }
+                for (int i = 0; i < 4; ++i)
+                    o[i] = pack_bf16x2(acc[u][2 * i], acc[u][2 * i + 1]);
             } else {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    acc[i] = fmaf(w, __uint_as_float(v[i]), acc[i]);
+                    o[i] = __float_as_uint(acc[u][i]);
             }
+            out[n * chunks + c + u * kWave] = o;
         }
-        u32x4 o;
-        if (kBf16) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                o[i] = pack_bf16x2(acc[2 * i], acc[2 * i + 1]);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                o[i] = __float_as_uint(acc[i]);
-        }
-        out[n * chunks + c] = o;
-    }
+    };
+    int c = lane;
+    for (; c + 3 * kWave < chunks; c += 4 * kWave)
+        rows_of(std::integral_constant<int, 4>{}, c);
+    for (; c < chunks; c += kWave)
+        rows_of(std::integral_constant<int, 1>{}, c);
 }
 
 int launch_permute(const void *x, int64_t row_bytes, int64_t N, int K, const int32_t *slot_of_row,
