@@ -45,10 +45,21 @@ __device__ __forceinline__ int32_t clamped_rows(const int32_t *seg_offsets, int 
     return (int32_t)(hi - lo);
 }
 
+// One launch builds the tables of both GEMMs: blockIdx.y picks the set of arguments.
+struct TableArgs {
+    int n_tiles, max_tiles;
+    TileTableHeader *hdr;
+    TileEntry *table;
+};
+
 __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
-    const int32_t *__restrict__ seg_offsets, int E_local, int64_t M, int BM, int n_tiles, int light_rows,
-    int max_tiles, TileTableHeader *__restrict__ hdr, TileEntry *__restrict__ table)
+    const int32_t *__restrict__ seg_offsets, int E_local, int64_t M, int BM, int light_rows,
+    TableArgs gemm1, TableArgs gemm2)
 {
+    const TableArgs &args = blockIdx.y == 0 ? gemm1 : gemm2;
+    const int n_tiles = args.n_tiles, max_tiles = args.max_tiles;
+    TileTableHeader *__restrict__ hdr = args.hdr;
+    TileEntry *__restrict__ table = args.table;
     __shared__ int32_t start[2][MOE_MAX_EXPERTS + 1]; // first tile of each expert in the heavy [0] / light [1] stream
     __shared__ int32_t wave_tot[2][kSchedThreads / kWave];
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
@@ -349,12 +360,10 @@ int launch_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
         return MOE_OK; // the fp32 kernels look their expert up per row
     const FfnPlan p = make_plan(M, H, F, E_local);
     const FfnWorkspace k = carve(p, ws);
-    hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(k.max1, kSchedThreads)),
-                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles1, kLightRows, k.max1,
-                       k.hdr1, k.tab1);
-    hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(k.max2, kSchedThreads)),
-                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, p.n_tiles2, kLightRows, k.max2,
-                       k.hdr2, k.tab2);
+    const int max_both = k.max1 > k.max2 ? k.max1 : k.max2;
+    hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(max_both, kSchedThreads), 2),
+                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, kLightRows,
+                       TableArgs{p.n_tiles1, k.max1, k.hdr1, k.tab1}, TableArgs{p.n_tiles2, k.max2, k.hdr2, k.tab2});
     return check_launch("moe_ffn_schedule");
 }
 
