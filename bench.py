@@ -249,6 +249,29 @@ def main():
                              "permute_frac": gbs_perm / PEAK_HBM_GBS, "combine_frac": gbs_comb / PEAK_HBM_GBS},
         "step_breakdown_us": us,
     }
+    # Address resolution alone, stable order against arrival order (atomic row pointers), same inputs.
+    st0 = layer.sets[0]
+    reps = 20
+    la = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for timed in (False, True):
+        if timed:
+            la[0].record()
+        for _ in range(reps):
+            hub.moe_dispatch_layout(st0["idx"], E, G, st0["cnt"], st0["off"], st0["dcnt"], st0["doff"], st0["slot"],
+                                    st0["row"], layer.layout_ws)
+        if timed:
+            la[1].record()
+        for _ in range(reps):
+            hub.moe_dispatch_layout_arrival(st0["idx"], E, G, st0["cnt"], st0["off"], st0["dcnt"], st0["doff"],
+                                            st0["slot"], st0["row"])
+        if timed:
+            la[2].record()
+    # leave the stable layout in the buffers for what follows
+    hub.moe_dispatch_layout(st0["idx"], E, G, st0["cnt"], st0["off"], st0["dcnt"], st0["doff"], st0["slot"],
+                            st0["row"], layer.layout_ws)
+    torch.cuda.synchronize()
+    result["layout_order"] = {"stable_us": la[0].elapsed_time(la[1]) * 1e3 / reps,
+                              "arrival_us": la[1].elapsed_time(la[2]) * 1e3 / reps}
     if not layer.ep:
         # Variant without a dispatch row move (a single device that computes every expert needs no send
         # buffer): the gate/up GEMM gathers its rows from x.  Reported beside the layer, not as `value`.

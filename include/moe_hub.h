@@ -110,6 +110,25 @@ int moe_dispatch_layout(const int32_t *topk_idx, int64_t N, int K, int E, int G,
                         void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Address resolution in arrival order (the allocation unit of Section IV-A3: a row
+ * pointer per region, read and incremented atomically by each arriving row, which
+ * packs rows densely whatever order they come in; the flat row number kept in
+ * row_of_slot is the source information of Section IV-A4 that the combine needs).
+ * Counts, offsets and the per-destination view are exactly those of
+ * moe_dispatch_layout; slot_of_row / row_of_slot are again inverse bijections and
+ * every row lands inside its expert's region, but the order of rows inside a
+ * region is the order in which their atomics were served: it is not unique and may
+ * differ from call to call.  Every later step accepts either layout, and the
+ * layer's output does not depend on the choice: an expert row's result does not
+ * depend on its slot, and moe_combine sums in ascending k.
+ * Arguments as in moe_dispatch_layout; no workspace.
+ */
+int moe_dispatch_layout_arrival(const int32_t *topk_idx, int64_t N, int K, int E, int G,
+                                int32_t *expert_counts, int32_t *expert_offsets,
+                                int32_t *dest_counts, int32_t *dest_offsets,
+                                int32_t *slot_of_row, int32_t *row_of_slot, void *stream);
+
+/*
  * Dispatch, local half (Section II-A, step 2): xp[slot_of_row[n*K+k], :] = x[n, :],
  * a bitwise copy of each token row into each of its K slots.  The result is
  * expert-contiguous and therefore destination-contiguous: segment

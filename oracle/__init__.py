@@ -113,6 +113,26 @@ def layout(topk_idx: np.ndarray, E: int, G: int) -> dict:
     return out
 
 
+def layout_arrival(topk_idx: np.ndarray, E: int, G: int, arrival: np.ndarray) -> dict:
+    """Layout with rows packed in the order `arrival` lists them (flat rows, a permutation)."""
+    topk_idx = _c(topk_idx, np.int32)
+    N, K = topk_idx.shape
+    R = N * K
+    arrival = _c(arrival, np.int32)
+    assert E % G == 0 and arrival.shape == (R,)
+    assert np.array_equal(np.sort(arrival), np.arange(R, dtype=np.int32))
+    assert topk_idx.size == 0 or (topk_idx.min() >= 0 and topk_idx.max() < E)
+    out = dict(
+        expert_counts=np.empty(E, np.int32), expert_offsets=np.empty(E + 1, np.int32),
+        dest_counts=np.empty(G, np.int32), dest_offsets=np.empty(G + 1, np.int32),
+        slot_of_row=np.empty(R, np.int32), row_of_slot=np.empty(R, np.int32))
+    _load().oracle_layout_arrival(_p(topk_idx), ctypes.c_int64(N), ctypes.c_int(K), ctypes.c_int(E),
+                                  ctypes.c_int(G), _p(arrival), _p(out["expert_counts"]),
+                                  _p(out["expert_offsets"]), _p(out["dest_counts"]),
+                                  _p(out["dest_offsets"]), _p(out["slot_of_row"]), _p(out["row_of_slot"]))
+    return out
+
+
 def permute(x: np.ndarray, K: int, slot_of_row: np.ndarray) -> np.ndarray:
     x = _c(x)
     N, H = x.shape

@@ -25,7 +25,8 @@
  * Pins (tests/test_oracle_*.py): exact-rational brute force for R64 on tiny
  * inputs and fp64 dot products; stable sort of (-logit, index) pairs for the
  * selection; library softmax; numpy bincount / cumsum / stable argsort and an
- * O(R^2) rank count for the layout; float64 library matmuls, linearity and
+ * O(R^2) rank count for the layout (and, for its arrival-order form, a stable
+ * argsort of the experts taken in arrival order); float64 library matmuls, linearity and
  * equivariance for the FFN; identity experts for the combine.
  */
 #include <math.h>
@@ -183,6 +184,51 @@ void oracle_layout(const int32_t *topk_idx, int64_t N, int K, int E, int G,
         row_of_slot[slot] = (int32_t)r;
     }
     free(cursor);
+}
+
+/* ---------------------------------------------------------------------- *
+ * The same address resolution with the allocation unit of Section IV-A3 in
+ * place of the stable order: each region has a row pointer; an arriving row
+ * takes the pointer's value as its local row id and increments it, so rows
+ * are packed densely in the order they arrive.  arrival[i] is the flat row
+ * that arrives i-th (a permutation of 0..R-1).  Region bases are the same
+ * exclusive scan of the counts as above (counts do not depend on the
+ * order); slot = base[e] + local row id (the address formula of that
+ * section with RowSize factored out).  row_of_slot is the source
+ * information of Section IV-A4.
+ * ---------------------------------------------------------------------- */
+void oracle_layout_arrival(const int32_t *topk_idx, int64_t N, int K, int E, int G,
+                           const int32_t *arrival,
+                           int32_t *expert_counts, int32_t *expert_offsets,
+                           int32_t *dest_counts, int32_t *dest_offsets,
+                           int32_t *slot_of_row, int32_t *row_of_slot)
+{
+    int64_t R = N * K;
+    int Eg = E / G;
+    int32_t *row_pointer = (int32_t *)calloc((size_t)E, sizeof(int32_t));
+    int32_t *local_id = (int32_t *)malloc((size_t)(R > 0 ? R : 1) * sizeof(int32_t));
+    for (int64_t i = 0; i < R; ++i) {
+        int32_t r = arrival[i];
+        int e = topk_idx[r];
+        local_id[r] = row_pointer[e];
+        row_pointer[e] += 1;
+    }
+    expert_offsets[0] = 0;
+    for (int e = 0; e < E; ++e) {
+        expert_counts[e] = row_pointer[e];
+        expert_offsets[e + 1] = expert_offsets[e] + row_pointer[e];
+    }
+    for (int g = 0; g <= G; ++g)
+        dest_offsets[g] = expert_offsets[g * Eg];
+    for (int g = 0; g < G; ++g)
+        dest_counts[g] = dest_offsets[g + 1] - dest_offsets[g];
+    for (int64_t r = 0; r < R; ++r) {
+        int32_t slot = expert_offsets[topk_idx[r]] + local_id[r];
+        slot_of_row[r] = slot;
+        row_of_slot[slot] = (int32_t)r;
+    }
+    free(local_id);
+    free(row_pointer);
 }
 
 /* ---------------------------------------------------------------------- *

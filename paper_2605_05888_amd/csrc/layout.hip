@@ -91,22 +91,11 @@ __global__ __launch_bounds__(kWave) void layout_scan_units(int32_t *__restrict__
         expert_counts[e] = running;
 }
 
-__global__ __launch_bounds__(kWave *kWavesPerBlock) void layout_assign_slots(
-    const int32_t *__restrict__ idx, int64_t R, int E, int G, int nbits, int U,
-    const int32_t *__restrict__ unit_base, const int32_t *__restrict__ expert_counts,
-    int32_t *__restrict__ expert_offsets, int32_t *__restrict__ dest_counts,
-    int32_t *__restrict__ dest_offsets, int32_t *__restrict__ slot_of_row,
-    int32_t *__restrict__ row_of_slot)
+// One wavefront: off[0..E] = exclusive scan of expert_counts[0..E), off[E] = total.
+// Each lane owns a contiguous run of experts.
+__device__ __forceinline__ void region_offsets(const int32_t *__restrict__ expert_counts, int E,
+                                               int lane, int32_t *off)
 {
-    extern __shared__ int32_t lds[];
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    int32_t *cursor = lds + wave * (E + 1);
-    const int u = blockIdx.x * kWavesPerBlock + wave;
-    const bool writer = (blockIdx.x == 0 && wave == 0);
-    if (u >= U && !writer)
-        return;
-
-    // region offsets: exclusive scan of the counts; lane owns a contiguous run of experts
     const int per = (E + kWave - 1) / kWave;
     const int e_lo = lane * per;
     int32_t mine = 0;
@@ -122,23 +111,49 @@ __global__ __launch_bounds__(kWave *kWavesPerBlock) void layout_assign_slots(
     int32_t run = inc - mine;
     for (int j = 0; j < per; ++j)
         if (e_lo + j < E) {
-            cursor[e_lo + j] = run;
+            off[e_lo + j] = run;
             run += expert_counts[e_lo + j];
         }
     if (lane == kWave - 1)
-        cursor[E] = inc; // total = N*K
+        off[E] = inc; // total = N*K
+}
 
-    if (writer) {
-        for (int e = lane; e <= E; e += kWave)
-            expert_offsets[e] = cursor[e];
-        const int Eg = E / G;
-        for (int g = lane; g <= G; g += kWave) {
-            int32_t o = cursor[g * Eg];
-            dest_offsets[g] = o;
-            if (g < G)
-                dest_counts[g] = cursor[(g + 1) * Eg] - o;
-        }
+// Block 0's first wavefront publishes the offsets and the per-destination view.
+__device__ __forceinline__ void write_region_tables(const int32_t *off, int E, int G, int lane,
+                                                    int32_t *__restrict__ expert_offsets,
+                                                    int32_t *__restrict__ dest_counts,
+                                                    int32_t *__restrict__ dest_offsets)
+{
+    for (int e = lane; e <= E; e += kWave)
+        expert_offsets[e] = off[e];
+    const int Eg = E / G;
+    for (int g = lane; g <= G; g += kWave) {
+        int32_t o = off[g * Eg];
+        dest_offsets[g] = o;
+        if (g < G)
+            dest_counts[g] = off[(g + 1) * Eg] - o;
     }
+}
+
+__global__ __launch_bounds__(kWave *kWavesPerBlock) void layout_assign_slots(
+    const int32_t *__restrict__ idx, int64_t R, int E, int G, int nbits, int U,
+    const int32_t *__restrict__ unit_base, const int32_t *__restrict__ expert_counts,
+    int32_t *__restrict__ expert_offsets, int32_t *__restrict__ dest_counts,
+    int32_t *__restrict__ dest_offsets, int32_t *__restrict__ slot_of_row,
+    int32_t *__restrict__ row_of_slot)
+{
+    extern __shared__ int32_t lds[];
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    int32_t *cursor = lds + wave * (E + 1);
+    const int u = blockIdx.x * kWavesPerBlock + wave;
+    const bool writer = (blockIdx.x == 0 && wave == 0);
+    if (u >= U && !writer)
+        return;
+
+    region_offsets(expert_counts, E, lane, cursor);
+
+    if (writer)
+        write_region_tables(cursor, E, G, lane, expert_offsets, dest_counts, dest_offsets);
     if (u >= U)
         return;
 
@@ -184,6 +199,106 @@ int launch_layout(const int32_t *topk_idx, int64_t R, int E, int G, int32_t *exp
                        topk_idx, R, E, G, nbits, U, unit_hist, expert_counts, expert_offsets,
                        dest_counts, dest_offsets, slot_of_row, row_of_slot);
     return check_launch("moe_dispatch_layout");
+}
+
+// ---------------------------------------------------------------------------
+// Arrival-order variant (Section IV-A3): every region has a row pointer that an
+// arriving row reads and increments atomically, so rows are packed densely in
+// whatever order they arrive.  Here the regions keep their scan-derived bases (the
+// counts are the same whatever the order), a row "arrives" when its wavefront
+// reaches its atomic, and the flat row number is the source information that
+// Section IV-A4 carries with each row (row_of_slot).
+//   pass 1  rank[r] = row pointer of expert idx[r] before the increment
+//   pass 2  slot = offset[e] + rank; both maps written
+// ---------------------------------------------------------------------------
+constexpr int kArrivalThreads = 256;
+constexpr int kArrivalRowsPerThread = 4;
+
+__global__ void layout_clear_counts(int32_t *__restrict__ counts, int E)
+{
+    int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < E)
+        counts[e] = 0;
+}
+
+__global__ __launch_bounds__(kArrivalThreads) void arrival_take_rank(
+    const int32_t *__restrict__ idx, int64_t R, int E,
+    int32_t *__restrict__ row_pointer, int32_t *__restrict__ rank)
+{
+    // Two levels of row pointers: the rows of a workgroup first draw from pointers in LDS, then
+    // the workgroup draws one range per expert from the global pointer and rebases its rows.
+    extern __shared__ int32_t group_pointer[]; // E
+    for (int e = threadIdx.x; e < E; e += kArrivalThreads)
+        group_pointer[e] = 0;
+    __syncthreads();
+    const int64_t r0 = (int64_t)blockIdx.x * (kArrivalThreads * kArrivalRowsPerThread);
+    int expert[kArrivalRowsPerThread];
+    int32_t local[kArrivalRowsPerThread];
+#pragma unroll
+    for (int j = 0; j < kArrivalRowsPerThread; ++j) {
+        const int64_t r = r0 + j * kArrivalThreads + threadIdx.x;
+        int e = (r < R) ? idx[r] : -1;
+        expert[j] = (e >= 0 && e < E) ? e : -1;
+        local[j] = (expert[j] >= 0) ? atomicAdd(&group_pointer[expert[j]], 1) : 0;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += kArrivalThreads) {
+        int32_t c = group_pointer[e];
+        if (c > 0)
+            group_pointer[e] = atomicAdd(&row_pointer[e], c);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kArrivalRowsPerThread; ++j) {
+        const int64_t r = r0 + j * kArrivalThreads + threadIdx.x;
+        if (expert[j] >= 0)
+            rank[r] = group_pointer[expert[j]] + local[j];
+    }
+}
+
+__global__ __launch_bounds__(kArrivalThreads) void arrival_place_rows(
+    const int32_t *__restrict__ idx, int64_t R, int E, int G,
+    const int32_t *__restrict__ expert_counts, int32_t *__restrict__ expert_offsets,
+    int32_t *__restrict__ dest_counts, int32_t *__restrict__ dest_offsets,
+    int32_t *__restrict__ slot_of_row, int32_t *__restrict__ row_of_slot)
+{
+    extern __shared__ int32_t off[]; // E + 1
+    if (threadIdx.x < kWave) {
+        region_offsets(expert_counts, E, threadIdx.x, off);
+        if (blockIdx.x == 0)
+            write_region_tables(off, E, G, threadIdx.x, expert_offsets, dest_counts, dest_offsets);
+    }
+    __syncthreads();
+    const int64_t r0 = (int64_t)blockIdx.x * (kArrivalThreads * kArrivalRowsPerThread);
+#pragma unroll
+    for (int j = 0; j < kArrivalRowsPerThread; ++j) {
+        const int64_t r = r0 + j * kArrivalThreads + threadIdx.x;
+        if (r >= R)
+            continue;
+        int e = idx[r];
+        if (e < 0 || e >= E)
+            continue;
+        int32_t slot = off[e] + slot_of_row[r]; // slot_of_row holds the rank of pass 1
+        slot_of_row[r] = slot;
+        row_of_slot[slot] = (int32_t)r;
+    }
+}
+
+int launch_layout_arrival(const int32_t *topk_idx, int64_t R, int E, int G, int32_t *expert_counts,
+                          int32_t *expert_offsets, int32_t *dest_counts, int32_t *dest_offsets,
+                          int32_t *slot_of_row, int32_t *row_of_slot, hipStream_t st)
+{
+    const int64_t per_block = kArrivalThreads * kArrivalRowsPerThread;
+    const int blocks = (int)ceil_div(R, per_block);
+    hipLaunchKernelGGL(layout_clear_counts, dim3((int)ceil_div(E, 256)), dim3(256), 0, st,
+                       expert_counts, E);
+    if (blocks > 0)
+        hipLaunchKernelGGL(arrival_take_rank, dim3(blocks), dim3(kArrivalThreads),
+                           E * sizeof(int32_t), st, topk_idx, R, E, expert_counts, slot_of_row);
+    hipLaunchKernelGGL(arrival_place_rows, dim3(blocks > 0 ? blocks : 1), dim3(kArrivalThreads),
+                       (E + 1) * sizeof(int32_t), st, topk_idx, R, E, G, expert_counts,
+                       expert_offsets, dest_counts, dest_offsets, slot_of_row, row_of_slot);
+    return check_launch("moe_dispatch_layout_arrival");
 }
 
 }  // namespace moe

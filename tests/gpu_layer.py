@@ -50,6 +50,21 @@ def gpu_layout(idx, E, G):
     return out
 
 
+def gpu_layout_arrival(idx, E, G):
+    N, K = idx.shape
+    R = N * K
+    out = dict(
+        expert_counts=torch.full((E,), -7, dtype=torch.int32, device=DEV),
+        expert_offsets=torch.full((E + 1,), -7, dtype=torch.int32, device=DEV),
+        dest_counts=torch.full((G,), -7, dtype=torch.int32, device=DEV),
+        dest_offsets=torch.full((G + 1,), -7, dtype=torch.int32, device=DEV),
+        slot_of_row=torch.full((R,), -7, dtype=torch.int32, device=DEV),
+        row_of_slot=torch.full((R,), -7, dtype=torch.int32, device=DEV))
+    hub.moe_dispatch_layout_arrival(idx, E, G, out["expert_counts"], out["expert_offsets"], out["dest_counts"],
+                                    out["dest_offsets"], out["slot_of_row"], out["row_of_slot"])
+    return out
+
+
 def gpu_permute(x, K, lay):
     N, H = x.shape
     xp = torch.zeros((N * K, H), dtype=x.dtype, device=DEV)

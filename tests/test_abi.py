@@ -20,6 +20,7 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert set(names) == {"moe_last_error", "moe_workspace_bytes", "moe_route", "moe_dispatch_layout",
+                          "moe_dispatch_layout_arrival",
                           "moe_permute", "moe_grouped_ffn", "moe_combine",
                           "moe_ffn_schedule", "moe_ffn_gate_up", "moe_ffn_gate_up_gather", "moe_ffn_down"}
     lib = ctypes.CDLL(hub.lib_path()) if os.path.exists(hub.lib_path()) else hub.load_library()
@@ -61,6 +62,10 @@ ALIGNED = 0x1000   # a fake, well-aligned, never-dereferenced pointer: every cas
                                      ALIGNED, 4, None), -3, "workspace"),
     (lambda L: L.moe_dispatch_layout(ALIGNED, 4, 2, 8, 2, None, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED,
                                      ALIGNED, 1 << 20, None), -1, "NULL"),
+    (lambda L: L.moe_dispatch_layout_arrival(ALIGNED, 4, 2, 8, 3, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED,
+                                             ALIGNED, None), -1, "divide"),
+    (lambda L: L.moe_dispatch_layout_arrival(ALIGNED, 4, 2, 8, 2, ALIGNED, ALIGNED, ALIGNED, ALIGNED, None,
+                                             ALIGNED, None), -1, "NULL"),
     (lambda L: L.moe_grouped_ffn(ALIGNED, hub.BF16, 64, 64, 64, 0, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED,
                                  ALIGNED, 1 << 30, None), -1, "E_local"),
     (lambda L: L.moe_grouped_ffn(ALIGNED, hub.BF16, 64, 64, 64, 2, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED,

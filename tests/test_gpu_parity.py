@@ -111,6 +111,31 @@ def test_layout_parity(G, N, E, K, Gd, skew):
         assert np.array_equal(G.host(again[k]), want[k]), k
 
 
+@pytest.mark.parametrize("N,E,K,Gd,skew", LAYOUT_CASES)
+def test_arrival_order_layout_unique_parts_exact_and_slots_valid(G, N, E, K, Gd, skew):
+    """Row order inside a region is not unique: counts, offsets and destinations must equal the oracle's,
+    the slot maps must be inverse bijections that keep every row inside its expert's region."""
+    import moe_inputs.device as mid
+    from layout_checks import check_layout_is_valid
+    _say("arrival layout", N, E, K, Gd, skew)
+    rng = np.random.default_rng(N + E)
+    idx = _random_idx(rng, N, E, K, skew) if N else np.zeros((0, K), np.int32)
+    want = oracle.layout(idx, E, Gd)
+    for _ in range(2):                                           # the second call finds used counters
+        got = {k: G.host(v) for k, v in G.gpu_layout_arrival(mid.to_device(idx).reshape(N, K), E, Gd).items()}
+        for k in ("expert_counts", "expert_offsets", "dest_counts", "dest_offsets"):
+            assert np.array_equal(got[k], want[k]), k
+        check_layout_is_valid(idx, E, Gd, got)
+
+
+def test_arrival_order_layout_all_rows_to_one_expert(G):
+    import moe_inputs.device as mid
+    from layout_checks import check_layout_is_valid
+    idx = np.full((3000, 1), 37, np.int32)                       # one row pointer takes every arrival
+    got = {k: G.host(v) for k, v in G.gpu_layout_arrival(mid.to_device(idx), 64, 8).items()}
+    check_layout_is_valid(idx, 64, 8, got)
+
+
 def test_layout_all_rows_to_one_expert(G):
     import moe_inputs.device as mid
     idx = np.full((3000, 1), 37, np.int32)
@@ -324,6 +349,36 @@ def test_whole_layer_parity(G, name):
     G.check_close(G.host(y), o_y, *tol, what="y")
     ma, rl = G.check_close(G.host(out), o_out, *tol, what="out")
     _say("   out max-abs %.3e rel-L2 %.3e" % (ma, rl))
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_whole_layer_over_arrival_order_layout(G, name):
+    """The layer's output does not depend on the order of rows inside a region: over the arrival-order
+    layout it is bit for bit the output over the stable layout, and within tolerance of the oracle."""
+    import moe_inputs.device as mid
+    from layout_checks import check_layout_is_valid
+    cfg = SMALL[name]
+    _say("layer, arrival order", cfg)
+    x, Wr = mi.host_tensor(cfg, mi.STREAM_X), mi.host_tensor(cfg, mi.STREAM_W_ROUTER)
+    Wg, Wu, Wd = (mi.host_tensor(cfg, s) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    bias = mi.router_bias(cfg)
+    o_idx, o_w, _ = oracle.route(x, Wr, bias, cfg.K, cfg.score_mode)
+    o_lay = oracle.layout(o_idx, cfg.E, cfg.G)
+    o_y = oracle.ffn_rows(oracle.permute(x, cfg.K, o_lay["slot_of_row"]), o_lay["expert_offsets"], Wg, Wu, Wd)
+    o_out = oracle.combine(o_y, cfg.K, o_lay["slot_of_row"], o_w)
+    dx, dWg, dWu, dWd = (mid.to_device(t) for t in (x, Wg, Wu, Wd))
+    idx, w, _ = G.gpu_route(dx, mid.to_device(Wr), None if bias is None else mid.to_device(bias), cfg.K,
+                            cfg.score_mode, want_logits=False)
+    outs = []
+    for layout in (G.gpu_layout, G.gpu_layout_arrival):
+        lay = layout(idx, cfg.E, cfg.G)
+        check_layout_is_valid(o_idx, cfg.E, cfg.G, {k: G.host(v) for k, v in lay.items()})
+        xp = G.gpu_permute(dx, cfg.K, lay)
+        assert np.array_equal(G.host(xp)[G.host(lay["slot_of_row"])], np.repeat(x, cfg.K, axis=0))
+        y = G.gpu_ffn(xp, lay["expert_offsets"], dWg, dWu, dWd)
+        outs.append(G.host(G.gpu_combine(y, cfg.K, lay["slot_of_row"], w)))
+    assert np.array_equal(outs[0], outs[1])
+    G.check_close(outs[1], o_out, *G.tolerances(cfg), what="out over arrival-order layout")
 
 
 def test_expert_parallel_rank_share(G):

@@ -6,6 +6,7 @@ import pytest
 
 import moe_inputs as mi
 import oracle
+from layout_checks import check_layout_is_valid
 
 
 def _read_golden(path):
@@ -84,6 +85,75 @@ def test_layout_degenerate_cases():
     lay = oracle.layout(idx, 5, 1)
     assert list(lay["expert_counts"]) == [3] * 5
     assert np.array_equal(lay["row_of_slot"].reshape(5, 3), np.arange(15).reshape(3, 5).T)
+
+
+@pytest.mark.parametrize("N,E,K,G,skew", [(1, 4, 2, 2, False), (41, 8, 2, 4, False), (300, 32, 4, 8, True),
+                                          (120, 128, 8, 1, True)])
+def test_arrival_order_layout_is_the_stable_sort_of_the_arrival_sequence(N, E, K, G, skew):
+    """Row pointers that count arrivals (Section IV-A3) pack each region in arrival order: listing the
+    rows in arrival order and sorting them stably by expert (a library routine) gives row_of_slot."""
+    rng = np.random.default_rng(N + 31 * E)
+    idx = _random_idx(rng, N, E, K, skew)
+    flat = idx.ravel()
+    R = N * K
+    stable = oracle.layout(idx, E, G)
+    for order in ("identity", "reversed", "random"):
+        arrival = {"identity": np.arange(R), "reversed": np.arange(R)[::-1],
+                   "random": rng.permutation(R)}[order].astype(np.int32)
+        lay = oracle.layout_arrival(idx, E, G, arrival)
+        check_layout_is_valid(idx, E, G, lay)
+        assert np.array_equal(lay["row_of_slot"], arrival[np.argsort(flat[arrival], kind="stable")]), order
+        for name in ("expert_counts", "expert_offsets", "dest_counts", "dest_offsets"):
+            assert np.array_equal(lay[name], stable[name]), (order, name)     # order never moves a region
+        if order == "identity":                                               # in-order arrival = the stable layout
+            assert np.array_equal(lay["slot_of_row"], stable["slot_of_row"])
+        if order == "reversed":                                               # regions hold descending rows
+            for e in range(E):
+                seg = lay["row_of_slot"][lay["expert_offsets"][e]:lay["expert_offsets"][e + 1]]
+                assert np.all(np.diff(seg) < 0)
+    # the local row id of a row is the number of earlier arrivals at its expert (brute force)
+    pos = np.empty(R, np.int64)
+    pos[arrival] = np.arange(R)
+    for r in range(min(R, 200)):
+        earlier = np.count_nonzero((flat == flat[r]) & (pos < pos[r]))
+        assert lay["slot_of_row"][r] == lay["expert_offsets"][flat[r]] + earlier
+
+
+def test_validity_check_rejects_planted_mistakes():
+    rng = np.random.default_rng(5)
+    N, E, K, G = 50, 8, 2, 2
+    idx = _random_idx(rng, N, E, K)
+    good = oracle.layout_arrival(idx, E, G, rng.permutation(N * K).astype(np.int32))
+    check_layout_is_valid(idx, E, G, good)
+
+    def broken(**changes):
+        lay = {k: v.copy() for k, v in good.items()}
+        for k, f in changes.items():
+            f(lay[k])
+        with pytest.raises(AssertionError):
+            check_layout_is_valid(idx, E, G, lay)
+
+    def swap_across_regions(slot):                      # two rows of different experts trade slots
+        flat = idx.ravel()
+        a = 0
+        b = int(np.flatnonzero(flat != flat[0])[0])
+        slot[a], slot[b] = slot[b], slot[a]
+
+    def duplicate(slot):
+        slot[1] = slot[0]
+
+    def stale_inverse(row):
+        row[[0, 1]] = row[[1, 0]]
+
+    def miscount(c):
+        c[0] += 1
+
+    broken(slot_of_row=swap_across_regions)
+    broken(slot_of_row=duplicate)
+    broken(row_of_slot=stale_inverse)
+    broken(expert_counts=miscount)
+    broken(dest_offsets=miscount)
+    broken(expert_offsets=lambda o: o.__setitem__(slice(1, None), o[1:] + 1))
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.uint16])
