@@ -36,6 +36,14 @@ constexpr int kLightRows = 64;
 // prefetching tile geometry for those), and the rest.  Each class forms a stream of tiles (order:
 // expert, then column tile, then row tile); the table holds stream 0 (the rest), then stream 1
 // (light).  The GEMM's persistent workgroups draw from both.
+// Row tiles of an expert with `rows` rows: a remainder of at most `extra` rows rides with the last
+// full tile instead of forming a tile of its own.
+__device__ __forceinline__ int row_tiles(int32_t rows, int BM, int extra)
+{
+    const int full = rows / BM, rest = rows - full * BM;
+    return full > 0 && rest <= extra ? full : full + (rest > 0 ? 1 : 0);
+}
+
 __device__ __forceinline__ int32_t clamped_rows(const int32_t *seg_offsets, int e, int64_t M, int64_t &lo)
 {
     int64_t hi = seg_offsets[e + 1];
@@ -53,7 +61,7 @@ struct TableArgs {
 };
 
 __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
-    const int32_t *__restrict__ seg_offsets, int E_local, int64_t M, int BM, int light_rows,
+    const int32_t *__restrict__ seg_offsets, int E_local, int64_t M, int BM, int extra, int light_rows,
     TableArgs gemm1, TableArgs gemm2)
 {
     const TableArgs &args = blockIdx.y == 0 ? gemm1 : gemm2;
@@ -72,7 +80,7 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
         if (e < E_local) {
             int64_t lo;
             const int32_t rows = clamped_rows(seg_offsets, e, M, lo);
-            mine[rows <= light_rows ? 1 : 0] += (rows + BM - 1) / BM * n_tiles;
+            mine[rows <= light_rows ? 1 : 0] += row_tiles(rows, BM, extra) * n_tiles;
         }
     }
     int32_t inc[2] = {mine[0], mine[1]};
@@ -100,7 +108,7 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
             const int32_t rows = clamped_rows(seg_offsets, e, M, lo);
             start[0][e] = run[0];
             start[1][e] = run[1];
-            run[rows <= light_rows ? 1 : 0] += (rows + BM - 1) / BM * n_tiles;
+            run[rows <= light_rows ? 1 : 0] += row_tiles(rows, BM, extra) * n_tiles;
         }
     }
     if (tid == kSchedThreads - 1) { // the last thread's running sums are the totals
@@ -142,7 +150,7 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
         const int e = lo_e;
         int64_t lo;
         const int32_t n_rows_e = clamped_rows(seg_offsets, e, M, lo);
-        const int m_tiles = (n_rows_e + BM - 1) / BM;
+        const int m_tiles = row_tiles(n_rows_e, BM, extra);
         // Inside an expert the tiles go in blocks of kOrderRows x kOrderCols (row tiles x column
         // tiles): the 16 tiles an XCD takes together then share 4 weight tiles and 4 activation
         // tiles in its L2, instead of one and 16.
@@ -157,8 +165,11 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
         const int in_block = in_band - cb * kOrderCols * h;
         TileEntry t;
         t.expert = e;
-        t.n_tile = cb * kOrderCols + in_block / h;
-        t.m0 = (int32_t)lo + (rb * kOrderRows + in_block % h) * BM;
+        const int row_tile = rb * kOrderRows + in_block % h;
+        // rows that the expert's last tile computes beyond its BM
+        const int ext = row_tile == m_tiles - 1 && n_rows_e > m_tiles * BM ? n_rows_e - m_tiles * BM : 0;
+        t.n_tile = (cb * kOrderCols + in_block / h) | (ext << kTileColBits);
+        t.m0 = (int32_t)lo + row_tile * BM;
         t.m_end = (int32_t)lo + n_rows_e;
         table[L] = t;
     }
@@ -236,9 +247,9 @@ __global__ __launch_bounds__(256) void ffn_f32_down(const float *__restrict__ a,
 // ------------------------------------------------------------------------
 // Geometries.  Big: 256x256x64 tile, ring of 5 units (all 160 KiB of LDS); per window the 8 B loads
 // of a wavefront go out under the first two k-steps after the barrier, the 8 A loads under the
-// other two.  Shallow: 64x256x64 tile for experts with few rows, four (A, B) unit pairs, so that
+// other two.  An expert's last full tile also takes a remainder of up to 64 rows ("tall" tile).  Shallow: 64x256x64 tile for experts with few rows, four (A, B) unit pairs, so that
 // three K tiles of weights are in flight while one is multiplied. 
-template <bool kSwiglu> using BigTile = GemmCfg<256, 256, 2, 2, kSwiglu, 64, 5, 0x0044, 0x4400, 0>;
+template <bool kSwiglu> using BigTile = GemmCfg<256, 256, 2, 2, kSwiglu, 64, 5, 0x0044, 0x4400, 0, 64>;
 template <bool kSwiglu> using ShallowTile = GemmCfg<64, 256, 1, 4, kSwiglu, 64, 8, 0x1010, 0x2222, 1>;
 
 struct FfnPlan {
@@ -362,7 +373,7 @@ int launch_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     const FfnWorkspace k = carve(p, ws);
     const int max_both = k.max1 > k.max2 ? k.max1 : k.max2;
     hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(max_both, kSchedThreads), 2),
-                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, kLightRows,
+                       dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, BigTile<true>::kExtra, kLightRows,
                        TableArgs{p.n_tiles1, k.max1, k.hdr1, k.tab1}, TableArgs{p.n_tiles2, k.max2, k.hdr2, k.tab2});
     return check_launch("moe_ffn_schedule");
 }

@@ -48,8 +48,9 @@ struct TileEntry {
     int32_t expert; // local expert
     int32_t m0;     // first row of the tile
     int32_t m_end;  // end of the expert's segment (rows >= m_end are not written)
-    int32_t n_tile; // column tile
+    int32_t n_tile; // column tile; bits 24..: rows beyond BM that this tile also computes (tall tile)
 };
+constexpr int kTileColBits = 24;
 
 constexpr int kXcds = 8;
 constexpr int kMaxGemmWorkgroups = 896; // workgroups of the persistent grid (ticket words of a table)
@@ -84,6 +85,16 @@ __device__ __forceinline__ int stream_position(int xcd, int j, int patch)
 __device__ __forceinline__ float silu_mul(float g, float u)
 {
     return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
+}
+
+// One accumulator out of the accumulation registers, at this point of the program and no earlier:
+// left to itself the compiler copies a whole tile's accumulators into vector registers as soon as
+// the K loop ends, and everything else that is live there has to make room.
+__device__ __forceinline__ float acc_read(float a)
+{
+    float v;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+    return v;
 }
 
 // XOR key of a tile row with kChunks 16-byte chunks: equal logical chunks of any 8 and
@@ -161,10 +172,16 @@ constexpr int window_tail(int dist_a, int dist_b, int parts, bool a_needed)
 
 // One tile geometry: BM x BN output tile, WM x WN wavefronts, K tiles of kBK, LDS ring of kUnits
 // units, kDistA / kDistB the load schedule (see the kernel), kKind the tile stream it serves.
-template <int BM_, int BN_, int WM_, int WN_, bool kSwiglu, int kBK_, int kUnits_, int kDistA_, int kDistB_, int kKind_>
+// kExtra_ > 0 ("tall"): a tile may carry up to kExtra_ rows beyond its BM, the short remainder of
+// an expert's segment.  Those rows do not pass through LDS: every wavefront keeps one more 32-row
+// block of accumulators and fetches that block's operand straight into registers.
+template <int BM_, int BN_, int WM_, int WN_, bool kSwiglu, int kBK_, int kUnits_, int kDistA_, int kDistB_, int kKind_,
+          int kExtra_ = 0>
 struct GemmCfg {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, kBK = kBK_, kUnits = kUnits_;
-    static constexpr int kDistA = kDistA_, kDistB = kDistB_, kKind = kKind_;
+    static constexpr int kDistA = kDistA_, kDistB = kDistB_, kKind = kKind_, kExtra = kExtra_;
+    static constexpr bool kTall = kExtra_ > 0;
+    static_assert(kExtra_ == 0 || kExtra_ == 32 * WM_, "one extra 32-row block per wavefront row");
     static constexpr int kWaves = WM * WN;
     static constexpr int kThreads = kWaves * kWave;
     static constexpr int kWaveM = BM / WM;    // rows per wavefront
@@ -285,38 +302,61 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
     constexpr int kDistA = Cfg::kDistA, kDistB = Cfg::kDistB;
     constexpr int kChunks = Cfg::kChunks, kRowBytes = Cfg::kRowBytes, kKSteps = Cfg::kKSteps;
     constexpr int kDepth = Cfg::kDepth, kAheadA = Cfg::kAheadA;
+    constexpr bool kTall = Cfg::kTall;
     const int wm = wave / WN, wn = wave % WN;
 
     // ---- global->LDS loads (buffer_load_dwordx4 ... lds): the lane at 16-byte position p of its
     //      row fetches chunk p ^ key(row).  Buffer addressing keeps the per-lane part of the address
     //      in one 32-bit register (row offset inside the tile, the same for every tile and the whole
     //      K loop); the tile base sits in the scalar resource and the K offset in a scalar register.
-    const int ld_row = lane / kChunks, ld_pc = lane % kChunks;
     // (kGather: the row part of the offset differs from tile to tile and is looked up, a_off holds
     // the chunk part; cur_row / nxt_row hold the row parts of `cur` and `nxt`)
-    int a_off[Cfg::kAGroups];
-    uint32_t cur_row[Cfg::kAGroups], nxt_row[Cfg::kAGroups];
-#pragma unroll
-    for (int g = 0; g < Cfg::kAGroups; ++g) {
-        const int r = (wave * Cfg::kAGroups + g) * Cfg::kGroupRows + ld_row;
-        a_off[g] = ((kGather ? 0 : r * Kdim) + ((ld_pc ^ row_key<kChunks>(r)) * 8)) * 2;
-        cur_row[g] = nxt_row[g] = 0u;
-    }
     // B rows of one wavefront (kSwiglu): first half gate columns, second half the same up columns.
     // A load group never straddles the two halves, so its resource is wave-uniform.
-    int b_off[Cfg::kBGroups];
+    int a_off[Cfg::kAGroups], b_off[Cfg::kBGroups];
+    int x_off = 0;                   // tall tiles: the lane's part of the extra rows' operand address
+    int a_off0 = 0, b_off0 = 0;      // operand reads from LDS, see read_frags
+    int ld_row = 0, fr_x = 0;        // the lane's row inside a load group / inside a 32-row block
+    uint32_t cur_row[Cfg::kAGroups], nxt_row[Cfg::kAGroups];
 #pragma unroll
-    for (int g = 0; g < Cfg::kBGroups; ++g) {
-        const int r = (wave * Cfg::kBGroups + g) * Cfg::kGroupRows + ld_row;
-        int col;
-        if (kSwiglu) {
-            const int w = r / Cfg::kWaveN, jj = r % Cfg::kWaveN, half = Cfg::kWaveN / 2;
-            col = w * half + (jj % half);
-        } else {
-            col = r;
+    for (int g = 0; g < Cfg::kAGroups; ++g)
+        cur_row[g] = nxt_row[g] = 0u;
+    // The per-lane constants are worked out again for every output tile from a lane number the
+    // optimiser cannot see through.  Computed once, they (and those of the other geometry) would
+    // stay in registers of their own from the start of the kernel to its end, across epilogues
+    // that need every register they can get.
+    auto lane_setup = [&]() {
+        int lane = tid % kWave;
+        asm volatile("" : "+v"(lane));
+        ld_row = lane / kChunks;
+        const int ld_pc = lane % kChunks;
+#pragma unroll
+        for (int g = 0; g < Cfg::kAGroups; ++g) {
+            const int r = (wave * Cfg::kAGroups + g) * Cfg::kGroupRows + ld_row;
+            a_off[g] = ((kGather ? 0 : r * Kdim) + ((ld_pc ^ row_key<kChunks>(r)) * 8)) * 2;
         }
-        b_off[g] = (col * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8)) * 2;
-    }
+#pragma unroll
+        for (int g = 0; g < Cfg::kBGroups; ++g) {
+            const int r = (wave * Cfg::kBGroups + g) * Cfg::kGroupRows + ld_row;
+            int col;
+            if (kSwiglu) {
+                const int w = r / Cfg::kWaveN, jj = r % Cfg::kWaveN, half = Cfg::kWaveN / 2;
+                col = w * half + (jj % half);
+            } else {
+                col = r;
+            }
+            b_off[g] = (col * Kdim + ((ld_pc ^ row_key<kChunks>(r)) * 8)) * 2;
+        }
+        // operand reads: lane (i = lane%32, kg = lane/32) reads chunk (2*ks + kg) of row i of a block.
+        // Block and wavefront offsets are multiples of 32 rows, so the key depends on i only, and
+        // k-step ks is the k-step-0 offset with chunk bits flipped by 2*ks.
+        const int fr = lane % 32, kg = lane / 32;
+        const int key = row_key<kChunks>(fr);
+        a_off0 = (wm * Cfg::kWaveM + fr) * kRowBytes + ((kg ^ key) << 4);
+        b_off0 = (wn * Cfg::kWaveN + fr) * kRowBytes + ((kg ^ key) << 4);
+        fr_x = fr;
+        x_off = ((kGather ? 0 : (BM + wm * 32 + fr) * Kdim) + kg * 8) * 2;
+    };
     // With kDepth + kAheadA K tiles or more per output tile, the loads that would run past the
     // end of a tile's reduction fetch the first K tiles of the workgroup's next tile (if that is
     // of the same kind), so that tile starts with its operands in LDS.  (Shorter reductions
@@ -332,12 +372,14 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         const uint16_t *a, *b; // b: the gate (or only) weight rows; the up rows lie b1_delta further
         uint32_t a_bytes, b_bytes;
         int32_t m0, m_end, n0;
+        int32_t ext; // rows beyond BM (tall tiles)
     };
     auto operands_of = [&](int tile) {
-        Operands o = {A, B0, 0u, 0u, 0, 0, 0};
+        Operands o = {A, B0, 0u, 0u, 0, 0, 0, 0};
         if (tile >= 0) {
             const TileEntry te = table[tile];
-            const int n0 = te.n_tile * Cfg::kOutCols;
+            const int n0 = (te.n_tile & ((1 << kTileColBits) - 1)) * Cfg::kOutCols;
+            o.ext = kTall ? te.n_tile >> kTileColBits : 0;
             const int64_t rows_left = (int64_t)te.m_end - te.m0; // >= 1
             const int cols_left = Ndim - n0;                      // >= 1
             if (kGather) { // any row of A may be needed; rows past the segment get an offset past the end
@@ -371,7 +413,61 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         for (int g = 0; g < Cfg::kAGroups; ++g)
             row[g] = row[g] != ~0u ? row[g] / (uint32_t)gather_div * (uint32_t)(Kdim * 2) : gather_bytes;
     };
+    // ---- tall tiles: the lane's operand of the extra 32-row block of its wavefront row.  Lane
+    //      (i, kg) holds, for k-step ks, k = 16 ks + 8 kg .. + 8 of extra row 32 wm + i of the K tile
+    //      being multiplied: xa[ks].  It comes straight from memory: right after k-step ks has used
+    //      xa[ks], the load of the next K tile's xa[ks] goes out, one K tile ahead of its use.  The
+    //      loads, the instructions that consume them and the waits in between (counted like those of
+    //      the LDS loads) are written out by hand: the compiler would wait for the youngest load in
+    //      flight at the top of every K tile.  It therefore does not know that xa[ks] is not valid
+    //      until that wait, and must not copy these registers while a load is on its way.  It has no
+    //      reason to inside the K loop of such a tile, which is one basic block; at the tile's start
+    //      the operands of K tile 0 are loaded and waited for in one statement, and the loads behind
+    //      the last K tile fetch nothing.
+    constexpr int kXRegs = kTall ? kKSteps : 1;
+    u32x4 xa[kXRegs];
+#pragma unroll
+    for (int ks = 0; ks < kXRegs; ++ks)
+        xa[ks] = u32x4{0u, 0u, 0u, 0u};
+    uint32_t cur_xrow = 0u; // kGather: row part of the offset, per tile
+    auto gather_lookup_x = [&](const Operands &o, uint32_t &row) {
+        const int64_t m = (int64_t)o.m0 + BM + wm * 32 + fr_x;
+        row = m < o.m_end ? (uint32_t)gather_rows[m] : ~0u;
+    };
+    auto gather_offset_x = [&](uint32_t &row) {
+        row = row != ~0u ? row / (uint32_t)gather_div * (uint32_t)(Kdim * 2) : gather_bytes;
+    };
     using lds_ptr = __attribute__((address_space(3))) void *;
+    auto x_resource = [&](bool real) {
+        const uint64_t base = reinterpret_cast<uint64_t>(cur.a);
+        const uint32_t bytes =
+            real && cur.ext > 0 ? (kGather ? gather_bytes : (uint32_t)((BM + cur.ext) * Kdim * 2)) : 0u;
+        return u32x4{(uint32_t)base, (uint32_t)(base >> 32) & 0xffffu, bytes, 0x00020000u};
+    };
+    auto x_voffset = [&]() { return kGather ? (int)(cur_xrow + (uint32_t)x_off) : x_off; };
+    // xa[ks] <- K tile t of `cur`; past the last K tile a load of zero bytes, which keeps the number
+    // of loads per K tile fixed and touches no memory
+    auto load_x = [&](auto ks_tag, int t) {
+        constexpr int ks = decltype(ks_tag)::value;
+        const u32x4 rs = x_resource(t < KT);
+        const int voff = x_voffset(), soff = t * (kBK * 2) + ks * 32;
+        u32x4 &dst = xa[ks]; // (a generic lambda does not capture through an asm operand)
+        asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "+v"(dst) : "v"(voff), "s"(rs), "s"(soff));
+    };
+    // all of K tile 0, complete on return (this also waits for every older load of the wavefront)
+    auto load_x_first = [&]() {
+        static_assert(!kTall || kXRegs == 4, "four k-steps per K tile");
+        const u32x4 rs = x_resource(true);
+        const int voff = x_voffset();
+        u32x4 &d0 = xa[0], &d1 = xa[kXRegs > 1 ? 1 : 0], &d2 = xa[kXRegs > 2 ? 2 : 0], &d3 = xa[kXRegs > 3 ? 3 : 0];
+        asm volatile("buffer_load_dwordx4 %0, %4, %5, 0 offen\n\t"
+                     "buffer_load_dwordx4 %1, %4, %5, 0 offen offset:32\n\t"
+                     "buffer_load_dwordx4 %2, %4, %5, 0 offen offset:64\n\t"
+                     "buffer_load_dwordx4 %3, %4, %5, 0 offen offset:96\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(d0), "=&v"(d1), "=&v"(d2), "=&v"(d3)
+                     : "v"(voff), "s"(rs));
+    };
     // K tile t of `cur`; past its last K tile (kTail only): K tile t - KT of `nxt`
     auto load_a_group = [&](int t, int unit, int g, auto tail_tag) {
         constexpr bool kTail = decltype(tail_tag)::value;
@@ -430,14 +526,6 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
     using tail_yes = std::integral_constant<bool, true>;
     using tail_no = std::integral_constant<bool, false>;
 
-    // ---- operand reads: lane (i = lane%32, kg = lane/32) reads chunk (2*ks + kg) of row i of a block.
-    //      Block and wavefront offsets are multiples of 32 rows, so the key depends on i only, and
-    //      k-step ks is the k-step-0 offset with chunk bits flipped by 2*ks.
-    const int fr = lane % 32, kg = lane / 32;
-    const int key = row_key<kChunks>(fr);
-    const int a_off0 = (wm * Cfg::kWaveM + fr) * kRowBytes + ((kg ^ key) << 4);
-    const int b_off0 = (wn * Cfg::kWaveN + fr) * kRowBytes + ((kg ^ key) << 4);
-
     bf16x8 fa[2][Cfg::kBlkM], fb[2][Cfg::kBlkN];
     // `act` = number of this wavefront's 32-row blocks that hold rows of the segment: blocks past
     // the end of a ragged segment are neither read nor multiplied.
@@ -465,13 +553,46 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
     };
 
+    // Tall tiles: the extra block row of this wavefront.  The 256 accumulators above fill the
+    // accumulation registers, so these live in ordinary vector registers and are multiplied by
+    // instructions written out by hand (the two leading wait states cover a vector-ALU write of an
+    // operand just before).
+    f32x16 accx[kTall ? Cfg::kBlkN : 1];
+    // loads issued between the load of xa[ks] and its use one K tile later: a K tile's worth but itself
+    constexpr int kXWait = Cfg::kLoadsPerTile + kXRegs - 1;
+    auto mfma_x = [&](int slot, auto ks_tag, int next_t) {
+        constexpr int ks = decltype(ks_tag)::value;
+        MOE_WAIT_VMCNT(kXWait);
+        const u32x4 &x = xa[ks];
+#pragma unroll
+        for (int j = 0; j < Cfg::kBlkN; ++j) {
+            f32x16 &c = accx[j];
+            const bf16x8 &w = fb[slot][j];
+            asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(w), "v"(x));
+        }
+        load_x(ks_tag, next_t);
+    };
+
     int u = 0; // ring position: A unit of the K tile to multiply next
 
     // One output tile: K loop, then the epilogue.  On entry K tile 0 of `cur` is in LDS (everyone's
     // loads, behind a barrier) and the windows before it have issued what they should.
-    auto run_tile = [&](auto act) {
+    auto run_tile = [&](auto act, auto ext_tag) {
         constexpr int kAct = decltype(act)::value;
+        constexpr bool kExt = decltype(ext_tag)::value; // the tile has extra rows
         constexpr int kMfma = kAct * Cfg::kBlkN, kReads = kAct ? kAct + Cfg::kBlkN : 0;
+        if constexpr (kExt) {
+#pragma unroll
+            for (int j = 0; j < Cfg::kBlkN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    accx[j][r] = 0.0f;
+            if constexpr (kGather) { // the extra rows of this tile: looked up here, a round trip per tall tile
+                gather_lookup_x(cur, cur_xrow);
+                gather_offset_x(cur_xrow);
+            }
+            load_x_first();
+        }
 #pragma unroll
         for (int i = 0; i < Cfg::kBlkM; ++i)
 #pragma unroll
@@ -488,6 +609,8 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
             issue_position(kt - 1, wrap(u + kUnits - 2), std::integral_constant<int, ks + 1>{}, tail_tag);
             read_frags(u, ks + 1, (ks + 1) & 1, act);
             mfma_all(ks & 1, act);
+            if constexpr (kExt)
+                mfma_x(ks & 1, ks_tag, kt + 1);
             interleave_under_mfma<kMfma, kReads, loads_at(ks + 1)>();
         };
         // The body is branch free (a branch around the LDS reads would make the compiler wait for
@@ -500,29 +623,46 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
             }
             __builtin_amdgcn_sched_barrier(0); // keep this k-step's MFMAs above the waits
             MOE_WAIT_LGKM0();                  // my reads of tile kt are complete
-            MOE_WAIT_VMCNT(kInFlight);         // my part of tile kt+1 has landed
+            MOE_WAIT_VMCNT(kInFlight + (kExt ? kXRegs - 1 : 0)); // my part of tile kt+1 has landed
             lds_barrier();                     // ... and everyone's; the units of tile kt are free
             issue_position(kt, u, std::integral_constant<int, 0>{}, tail_tag);
             read_frags(unit_a(u, 1), 0, 0, act); // past the last K tile: the next output tile's, read again there
             mfma_all((kKSteps - 1) & 1, act);
+            if constexpr (kExt)
+                mfma_x((kKSteps - 1) & 1, std::integral_constant<int, kKSteps - 1>{}, kt + 1);
             interleave_under_mfma<kMfma, kReads, loads_at(0)>();
             u = unit_a(u, 1);
         };
         // the last kDepth + kAheadA K tiles look past the end of this tile's reduction
-        const int k_split = KT - (kDepth + kAheadA);
-        if (k_split > 0)
-            ktile(0, tail_no{});
-        else
-            ktile(0, tail_yes{});
-        // The tile after `nxt`: thread 0 stored it before it reached the barrier of K tile 0.  The
-        // load is left in flight and looked at after the K loop.
-        uint64_t slot_v = read_slot();
-        if constexpr (kGather)
-            gather_offsets(nxt_row); // looked up before K tile 0, long landed; needed from k_split on
-        for (int kt = 1; kt < k_split; ++kt)
-            ktile(kt, tail_no{});
-        for (int kt = (k_split > 1 ? k_split : 1); kt < KT; ++kt)
-            ktile(kt, tail_yes{});
+        uint64_t slot_v = 0; // (sequence number 0: never a published one)
+        if constexpr (kExt) {
+            // one loop and nothing else between its K tiles, see xa; the next tile is looked up below
+            if constexpr (kGather)
+                gather_offsets(nxt_row);
+            for (int kt = 0; kt < KT; ++kt)
+                ktile(kt, tail_yes{});
+            // the (empty) loads behind the last K tile still write xa: they must have done so before
+            // the compiler, for which these registers are free from here on, puts anything else there
+            {
+                u32x4 &d0 = xa[0], &d1 = xa[kXRegs > 1 ? 1 : 0], &d2 = xa[kXRegs > 2 ? 2 : 0], &d3 = xa[kXRegs > 3 ? 3 : 0];
+                asm volatile("s_waitcnt vmcnt(0)" : "+v"(d0), "+v"(d1), "+v"(d2), "+v"(d3));
+            }
+        } else {
+            const int k_split = KT - (kDepth + kAheadA);
+            if (k_split > 0)
+                ktile(0, tail_no{});
+            else
+                ktile(0, tail_yes{});
+            // The tile after `nxt`: thread 0 stored it before it reached the barrier of K tile 0.  The
+            // load is left in flight and looked at after the K loop.
+            slot_v = read_slot();
+            if constexpr (kGather)
+                gather_offsets(nxt_row); // looked up before K tile 0, long landed; needed from k_split on
+            for (int kt = 1; kt < k_split; ++kt)
+                ktile(kt, tail_no{});
+            for (int kt = (k_split > 1 ? k_split : 1); kt < KT; ++kt)
+                ktile(kt, tail_yes{});
+        }
         // (if the store had not landed when the load ran, the sequence number is an older one)
         while (__builtin_amdgcn_readfirstlane((uint32_t)(slot_v >> 32)) != seq)
             slot_v = read_slot();
@@ -531,16 +671,19 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         // ---- epilogue.  Block (i, j), register r of lane l:
         //      output row    m = i*32 + l%32               (within the wavefront's rows)
         //      output column n = j*32 + 8*(r/4) + 4*(l/32) + r%4
+        // (acc_read is opaque to the compiler's hazard handling: the matrix pipe's last result may be
+        // read 18 wait states after its instruction at the earliest)
+        asm volatile("s_nop 15\n\ts_nop 3");
         int m_lane = lane % 32, n_lane = (lane / 32) * 4;
         // opaque to the optimiser: otherwise every column offset derived from them is kept in a
         // register of its own across the whole persistent loop
         asm volatile("" : "+v"(m_lane), "+v"(n_lane));
         constexpr int kOutBlkN = kSwiglu ? Cfg::kBlkN / 2 : Cfg::kBlkN;
-#pragma unroll
-        for (int i = 0; i < kAct; ++i) {
-            const int64_t m = (int64_t)cur.m0 + wm * Cfg::kWaveM + i * 32 + m_lane;
+        // one 32-row block row of accumulators -> row m of C
+        auto store_row = [&](int64_t m, const auto &blk, auto in_acc_regs) {
+            constexpr bool kAccRegs = decltype(in_acc_regs)::value;
             if (m >= cur.m_end)
-                continue;
+                return;
             uint16_t *crow = C + m * Ndim;
 #pragma unroll
             for (int j = 0; j < kOutBlkN; ++j) {
@@ -551,20 +694,39 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
                         continue;
                     float v[4];
 #pragma unroll
-                    for (int t = 0; t < 4; ++t)
-                        v[t] = kSwiglu ? silu_mul(acc[i][j][q * 4 + t], acc[i][j + kOutBlkN][q * 4 + t])
-                                       : acc[i][j][q * 4 + t];
+                    for (int t = 0; t < 4; ++t) {
+                        const int r = q * 4 + t;
+                        if constexpr (kSwiglu)
+                            v[t] = kAccRegs ? silu_mul(acc_read(blk[j][r]), acc_read(blk[j + kOutBlkN][r]))
+                                            : silu_mul(blk[j][r], blk[j + kOutBlkN][r]);
+                        else
+                            v[t] = kAccRegs ? acc_read(blk[j][r]) : blk[j][r];
+                    }
                     u32x2 o;
                     o[0] = pack_bf16x2(v[0], v[1]);
                     o[1] = pack_bf16x2(v[2], v[3]);
                     *reinterpret_cast<u32x2 *>(crow + col) = o;
                 }
+                // one block at a time: left alone, the scheduler first copies the whole tile out of the
+                // accumulation registers and needs some two hundred registers to hold it
+                __builtin_amdgcn_sched_barrier(0);
             }
+        };
+#pragma unroll
+        for (int i = 0; i < kAct; ++i)
+            store_row((int64_t)cur.m0 + wm * Cfg::kWaveM + i * 32 + m_lane, acc[i], std::true_type{});
+        if constexpr (kExt) {
+            // the hand-written instructions are opaque to the compiler's hazard handling: a result of
+            // the matrix pipe may be read by the vector ALU 18 wait states after the instruction at
+            // the earliest; the last one was issued before the block rows above were stored
+            asm volatile("s_nop 15\n\ts_nop 3" : "+v"(accx[0]), "+v"(accx[1]), "+v"(accx[Cfg::kBlkN - 2]), "+v"(accx[Cfg::kBlkN - 1]));
+            store_row((int64_t)cur.m0 + BM + wm * 32 + m_lane, accx, std::false_type{});
         }
     };
 
     bool primed = false; // K tile 0 of `cur` is in LDS already
     while (cur_t >= 0 && kind_of(cur_t) == Cfg::kKind) {
+        lane_setup();
         // the next tile's first K tiles ride behind this one's last
         const bool chain = warm && nxt_t >= 0 && kind_of(nxt_t) == Cfg::kKind;
         nxt = operands_of(chain ? nxt_t : -1);
@@ -576,6 +738,7 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
                 gather_lookup(cur, cur_row);
                 gather_offsets(cur_row);
             }
+
             // everything the windows before K tile 0 would have issued, then position 0 of the
             // window before it; K tile 0 landed
             u = 0;
@@ -598,16 +761,21 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         // rows of the segment inside this wavefront's part of the tile -> active 32-row blocks
         const int64_t rows = (int64_t)cur.m_end - ((int64_t)cur.m0 + wm * Cfg::kWaveM);
         const int active = rows <= 0 ? 0 : (rows >= Cfg::kWaveM ? Cfg::kBlkM : (int)((rows + 31) / 32));
-        if (active == Cfg::kBlkM)
-            run_tile(std::integral_constant<int, Cfg::kBlkM>{});
-        else if (active == 0)
-            run_tile(std::integral_constant<int, 0>{});
+        using ext_no = std::false_type;
+        using ext_yes = std::integral_constant<bool, kTall>;
+        if (active == Cfg::kBlkM) {
+            if (kTall && cur.ext > 0)
+                run_tile(std::integral_constant<int, Cfg::kBlkM>{}, ext_yes{});
+            else
+                run_tile(std::integral_constant<int, Cfg::kBlkM>{}, ext_no{});
+        } else if (active == 0)
+            run_tile(std::integral_constant<int, 0>{}, ext_no{});
         else if (active == 1)
-            run_tile(std::integral_constant<int, 1>{});
+            run_tile(std::integral_constant<int, 1>{}, ext_no{});
         else if (Cfg::kBlkM > 2 && active == 2)
-            run_tile(std::integral_constant<int, (Cfg::kBlkM > 2 ? 2 : 1)>{});
+            run_tile(std::integral_constant<int, (Cfg::kBlkM > 2 ? 2 : 1)>{}, ext_no{});
         else
-            run_tile(std::integral_constant<int, (Cfg::kBlkM > 3 ? 3 : 1)>{});
+            run_tile(std::integral_constant<int, (Cfg::kBlkM > 3 ? 3 : 1)>{}, ext_no{});
 
         // Thread 0 draws the tile that will follow `after_next` and leaves it in the other slot under
         // the next sequence number; the others look there after the next tile's first barrier.

@@ -211,6 +211,42 @@ def test_grouped_ffn_parity(G, M, H, F, E, dtype, empty):
     _say("   max-abs %.3e rel-L2 %.3e" % (ma, rl))
 
 
+def test_ffn_remainder_rows_riding_with_the_last_full_tile(G):
+    """An expert's remainder of up to 64 rows is computed by its last full tile, in other registers and by
+    other instructions than the tile's own 256 rows.  Sizes on both sides of every boundary; the result
+    must be within tolerance of the oracle, must not depend on which rows of an expert are the remainder
+    (segment reversed: same bits per row), and the gather form must give the same bits as permute + GEMM1."""
+    import moe_inputs.device as mid
+    import dataclasses
+    import torch
+    import paper_2605_05888_amd as hub
+    rows = [257, 287, 288, 289, 320, 321, 513, 832, 64, 65, 256, 255, 0, 300]
+    E, M = len(rows), sum(rows)
+    cfg = dataclasses.replace(mi.CONFIGS["tiny"], N=M, H=320, F=384, E=E, K=1, dtype=mi.BF16, seed=33)
+    _say("ffn, tall tiles", cfg)
+    seg = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    xp = mi.host_tensor(cfg, mi.STREAM_X)
+    Wg, Wu, Wd = (mi.host_tensor(cfg, s) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    dWg, dWu, dWd, dseg = (mid.to_device(t) for t in (Wg, Wu, Wd, seg))
+    y = G.host(G.gpu_ffn(mid.to_device(xp), dseg, dWg, dWu, dWd))
+    G.check_close(y, oracle.ffn_rows(xp, seg, Wg, Wu, Wd), *G.tolerances(cfg), what="ffn with tall tiles")
+    # every segment reversed: the remainder rows are now computed as ordinary rows of a full tile
+    rev = np.concatenate([np.arange(seg[e], seg[e + 1])[::-1] for e in range(E)]).astype(np.int32)
+    y_rev = G.host(G.gpu_ffn(mid.to_device(np.ascontiguousarray(xp[rev])), dseg, dWg, dWu, dWd))
+    assert np.array_equal(y_rev, y[rev])
+    # the same through the gather form of GEMM1: x holds the rows in reversed order, row_of_slot undoes it
+    code, dt = hub.BF16, torch.bfloat16
+    nb = hub.workspace_bytes(hub.OP_GROUPED_FFN, N=M, H=cfg.H, E=E, F=cfg.F, dtype=code)
+    ws = torch.zeros(nb, dtype=torch.uint8, device="cuda:0")
+    yg = torch.zeros((M, cfg.H), dtype=dt, device="cuda:0")
+    dx = mid.to_device(np.ascontiguousarray(xp[rev]))
+    hub.moe_ffn_schedule(code, M, cfg.H, cfg.F, dseg, ws)
+    hub.moe_ffn_gate_up_gather(dx.view(dt) if dx.dtype != dt else dx, 1, dseg, mid.to_device(rev), dWg, dWu, ws)
+    hub.moe_ffn_down(dseg, dWd, yg, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(G.host(yg), y)
+
+
 def test_ffn_steps_rerun_after_one_schedule(G):
     """The tile counters are handed back by the GEMM itself: after one moe_ffn_schedule the two
     GEMM steps can be launched again and again, and moe_grouped_ffn gives the same bits."""
