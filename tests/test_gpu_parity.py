@@ -211,6 +211,38 @@ def test_grouped_ffn_parity(G, M, H, F, E, dtype, empty):
     _say("   max-abs %.3e rel-L2 %.3e" % (ma, rl))
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_grouped_ffn_random_segmentations(G, seed):
+    """Expert sizes drawn around the tile boundaries (multiples of 256 plus or minus a few dozen rows, tiny
+    and empty experts in between): every mix of full, ragged, tall and shallow tiles, tiles chained or not
+    (H and F on both sides of three K tiles), against the oracle and, bit for bit, against a second run."""
+    import moe_inputs.device as mid
+    import dataclasses
+    rng = np.random.default_rng(1000 + seed)
+    E = int(rng.integers(3, 24))
+    rows = []
+    for _ in range(E):
+        kind = rng.integers(0, 5)
+        if kind == 0:
+            rows.append(int(rng.integers(0, 70)))                                   # shallow or empty
+        elif kind == 1:
+            rows.append(int(rng.integers(65, 256)))                                 # one ragged tile
+        else:
+            rows.append(int(256 * rng.integers(1, 4) + rng.integers(-70, 71)))      # around a boundary
+    rows = [max(r, 0) for r in rows]
+    M = sum(rows)
+    H, F = [(64, 128), (128, 64), (192, 320), (320, 192), (256, 256), (448, 128)][seed]
+    cfg = dataclasses.replace(mi.CONFIGS["tiny"], N=M, H=H, F=F, E=E, K=1, dtype=mi.BF16, seed=50 + seed)
+    _say("ffn, random segments", rows, H, F)
+    seg = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    xp = mi.host_tensor(cfg, mi.STREAM_X)
+    Wg, Wu, Wd = (mi.host_tensor(cfg, s) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    args = [mid.to_device(t) for t in (xp, seg, Wg, Wu, Wd)]
+    y = G.host(G.gpu_ffn(*args))
+    G.check_close(y, oracle.ffn_rows(xp, seg, Wg, Wu, Wd), *G.tolerances(cfg), what="ffn, random segments")
+    assert np.array_equal(G.host(G.gpu_ffn(*args)), y)
+
+
 def test_ffn_remainder_rows_riding_with_the_last_full_tile(G):
     """An expert's remainder of up to 64 rows is computed by its last full tile, in other registers and by
     other instructions than the tile's own 256 rows.  Sizes on both sides of every boundary; the result
