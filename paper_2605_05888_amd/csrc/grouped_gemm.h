@@ -35,7 +35,9 @@
 // one output tile, its loads already fetch the first K tiles of its next one.  The table has
 // two streams of tiles, served by two tile geometries inside the one kernel: 256x256 tiles, and
 // 64x256 tiles four K tiles deep for experts with at most 64 rows, which do little arithmetic
-// and live on how many bytes they keep in flight.
+// and live on how many bytes they keep in flight.  A 256-row tile can be "tall": the last full
+// tile of an expert also computes a remainder of up to 64 rows, against the B tiles it has in LDS
+// anyway, with the extra rows' operand and accumulators in vector registers (see GemmCfg).
 #pragma once
 
 #include <type_traits>
