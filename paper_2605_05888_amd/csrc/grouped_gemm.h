@@ -453,7 +453,7 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         constexpr int ks = decltype(ks_tag)::value;
         const u32x4 rs = x_resource(t < KT);
         const int voff = x_voffset(), soff = t * (kBK * 2) + ks * 32;
-        u32x4 &dst = xa[ks]; // (a generic lambda does not capture through an asm operand)
+        u32x4 &dst = xa[ks < kXRegs ? ks : 0]; // (a generic lambda does not capture through an asm operand)
         asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "+v"(dst) : "v"(voff), "s"(rs), "s"(soff));
     };
     // all of K tile 0, complete on return (this also waits for every older load of the wavefront)
@@ -565,7 +565,7 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
     auto mfma_x = [&](int slot, auto ks_tag, int next_t) {
         constexpr int ks = decltype(ks_tag)::value;
         MOE_WAIT_VMCNT(kXWait);
-        const u32x4 &x = xa[ks];
+        const u32x4 &x = xa[ks < kXRegs ? ks : 0];
 #pragma unroll
         for (int j = 0; j < Cfg::kBlkN; ++j) {
             f32x16 &c = accx[j];
@@ -666,7 +666,7 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
                 ktile(kt, tail_yes{});
         }
         // (if the store had not landed when the load ran, the sequence number is an older one)
-        while (__builtin_amdgcn_readfirstlane((uint32_t)(slot_v >> 32)) != seq)
+        while ((uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(slot_v >> 32)) != seq)
             slot_v = read_slot();
         after_next = (int)__builtin_amdgcn_readfirstlane((uint32_t)slot_v);
 
