@@ -295,6 +295,7 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
     const int64_t b1_delta = kSwiglu ? B1 - B0 : 0;
     int cur_t, nxt_t;   // the tile being computed and the next one, as table entries (-1: none)
     int after_next = -1; // the tile after `nxt`, picked up from the ticket slot inside the K loop
+    int drawn = -1;      // thread 0: the tile after that
 
     // ---- everything that depends on the tile geometry.  One call works through the workgroup's
     //      tiles as long as they are of this geometry's kind.
@@ -669,6 +670,11 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         while ((uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(slot_v >> 32)) != seq)
             slot_v = read_slot();
         after_next = (int)__builtin_amdgcn_readfirstlane((uint32_t)slot_v);
+        // Thread 0 draws the tile that will follow `after_next` now, so that the counter's round trip
+        // runs under the epilogue; the tile is published after it.
+        drawn = -1;
+        if (tid == 0 && after_next >= 0)
+            drawn = fetch_tile();
 
         // ---- epilogue.  Block (i, j), register r of lane l:
         //      output row    m = i*32 + l%32               (within the wavefront's rows)
@@ -779,11 +785,11 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         else
             run_tile(std::integral_constant<int, (Cfg::kBlkM > 3 ? 3 : 1)>{}, ext_no{});
 
-        // Thread 0 draws the tile that will follow `after_next` and leaves it in the other slot under
-        // the next sequence number; the others look there after the next tile's first barrier.
+        // Thread 0 leaves the tile it drew before the epilogue in the other slot under the next
+        // sequence number; the others look there after the next tile's first barrier.
         ++seq;
         if (tid == 0)
-            publish(after_next >= 0 ? fetch_tile() : -1);
+            publish(drawn);
         cur_t = nxt_t;
         nxt_t = after_next;
         if (chain) {
