@@ -50,7 +50,7 @@ def parse_args():
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a HIP graph (one graph of all buffer sets' steps)")
     ap.add_argument("--nbuf", type=int, default=0, help="activation buffer sets rotated per step (0 = auto)")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample (0 = skip)")
+    ap.add_argument("--cpu-seconds", type=float, default=18.0, help="target CPU time of the oracle sample (0 = skip)")
     return ap.parse_args()
 
 
