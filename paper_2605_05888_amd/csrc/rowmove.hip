@@ -74,7 +74,7 @@ __global__ __launch_bounds__(kWave *kTokensPerBlock) void combine_rows(
             u32x4 v[kU];
 #pragma unroll
             for (int u = 0; u < kU; ++u)
-                v[u] = src[u * kWave];
+                v[u] = __builtin_nontemporal_load(&src[u * kWave]); // read once: no need to keep it cached
 #pragma unroll
             for (int u = 0; u < kU; ++u) {
                 if (kBf16) {
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(kWave *kTokensPerBlock) void combine_rows(
                 for (int i = 0; i < 4; ++i)
                     o[i] = __float_as_uint(acc[u][i]);
             }
-            out[n * chunks + c + u * kWave] = o;
+            __builtin_nontemporal_store(o, &out[n * chunks + c + u * kWave]);
         }
     };
     int c = lane;
