@@ -183,7 +183,8 @@ struct GemmCfg {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, kBK = kBK_, kUnits = kUnits_;
     static constexpr int kDistA = kDistA_, kDistB = kDistB_, kKind = kKind_, kExtra = kExtra_;
     static constexpr bool kTall = kExtra_ > 0;
-    static_assert(kExtra_ == 0 || kExtra_ == 32 * WM_, "one extra 32-row block per wavefront row");
+    static_assert(kExtra_ == 0 || (kExtra_ == 32 * WM_ && WM_ == 2 && (BN_ / WN_ / 32) % 2 == 0),
+                  "one extra 32-row block per wavefront row, two wavefront rows that can share one block");
     static constexpr int kWaves = WM * WN;
     static constexpr int kThreads = kWaves * kWave;
     static constexpr int kWaveM = BM / WM;    // rows per wavefront
@@ -433,8 +434,9 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
     for (int ks = 0; ks < kXRegs; ++ks)
         xa[ks] = u32x4{0u, 0u, 0u, 0u};
     uint32_t cur_xrow = 0u; // kGather: row part of the offset, per tile
-    auto gather_lookup_x = [&](const Operands &o, uint32_t &row) {
-        const int64_t m = (int64_t)o.m0 + BM + wm * 32 + fr_x;
+    // (kHalf: at most 32 extra rows, one block that both wavefront rows work on, see run_tile)
+    auto gather_lookup_x = [&](const Operands &o, uint32_t &row, bool half) {
+        const int64_t m = (int64_t)o.m0 + BM + (half ? 0 : wm * 32) + fr_x;
         row = m < o.m_end ? (uint32_t)gather_rows[m] : ~0u;
     };
     auto gather_offset_x = [&](uint32_t &row) {
@@ -447,21 +449,23 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
             real && cur.ext > 0 ? (kGather ? gather_bytes : (uint32_t)((BM + cur.ext) * Kdim * 2)) : 0u;
         return u32x4{(uint32_t)base, (uint32_t)(base >> 32) & 0xffffu, bytes, 0x00020000u};
     };
-    auto x_voffset = [&]() { return kGather ? (int)(cur_xrow + (uint32_t)x_off) : x_off; };
+    auto x_voffset = [&](bool half) {
+        return kGather ? (int)(cur_xrow + (uint32_t)x_off) : x_off - (half ? wm * 32 * Kdim * 2 : 0);
+    };
     // xa[ks] <- K tile t of `cur`; past the last K tile a load of zero bytes, which keeps the number
     // of loads per K tile fixed and touches no memory
-    auto load_x = [&](auto ks_tag, int t) {
+    auto load_x = [&](auto ks_tag, int t, bool half) {
         constexpr int ks = decltype(ks_tag)::value;
         const u32x4 rs = x_resource(t < KT);
-        const int voff = x_voffset(), soff = t * (kBK * 2) + ks * 32;
+        const int voff = x_voffset(half), soff = t * (kBK * 2) + ks * 32;
         u32x4 &dst = xa[ks < kXRegs ? ks : 0]; // (a generic lambda does not capture through an asm operand)
         asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "+v"(dst) : "v"(voff), "s"(rs), "s"(soff));
     };
     // all of K tile 0, complete on return (this also waits for every older load of the wavefront)
-    auto load_x_first = [&]() {
+    auto load_x_first = [&](bool half) {
         static_assert(!kTall || kXRegs == 4, "four k-steps per K tile");
         const u32x4 rs = x_resource(true);
-        const int voff = x_voffset();
+        const int voff = x_voffset(half);
         u32x4 &d0 = xa[0], &d1 = xa[kXRegs > 1 ? 1 : 0], &d2 = xa[kXRegs > 2 ? 2 : 0], &d3 = xa[kXRegs > 3 ? 3 : 0];
         asm volatile("buffer_load_dwordx4 %0, %4, %5, 0 offen\n\t"
                      "buffer_load_dwordx4 %1, %4, %5, 0 offen offset:32\n\t"
@@ -563,17 +567,29 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
     f32x16 accx[kTall ? Cfg::kBlkN : 1];
     // loads issued between the load of xa[ks] and its use one K tile later: a K tile's worth but itself
     constexpr int kXWait = Cfg::kLoadsPerTile + kXRegs - 1;
-    auto mfma_x = [&](int slot, auto ks_tag, int next_t) {
+    auto mfma_x = [&](int slot, auto ks_tag, int next_t, auto half_tag) {
         constexpr int ks = decltype(ks_tag)::value;
+        constexpr bool kHalf = decltype(half_tag)::value;
         MOE_WAIT_VMCNT(kXWait);
         const u32x4 &x = xa[ks < kXRegs ? ks : 0];
+        if constexpr (kHalf) {
+            // one extra block row for the whole workgroup: wavefront row wm takes column blocks
+            // wm, wm + 2, ... of its wavefront column (for SwiGLU a gate block and its up block)
 #pragma unroll
-        for (int j = 0; j < Cfg::kBlkN; ++j) {
-            f32x16 &c = accx[j];
-            const bf16x8 &w = fb[slot][j];
-            asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(w), "v"(x));
+            for (int jj = 0; jj < Cfg::kBlkN / 2; ++jj) {
+                f32x16 &c = accx[jj];
+                const bf16x8 w = wm ? fb[slot][2 * jj + 1] : fb[slot][2 * jj];
+                asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(w), "v"(x));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < Cfg::kBlkN; ++j) {
+                f32x16 &c = accx[j];
+                const bf16x8 &w = fb[slot][j];
+                asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(w), "v"(x));
+            }
         }
-        load_x(ks_tag, next_t);
+        load_x(ks_tag, next_t, kHalf);
     };
 
     int u = 0; // ring position: A unit of the K tile to multiply next
@@ -582,7 +598,11 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
     // loads, behind a barrier) and the windows before it have issued what they should.
     auto run_tile = [&](auto act, auto ext_tag) {
         constexpr int kAct = decltype(act)::value;
-        constexpr bool kExt = decltype(ext_tag)::value; // the tile has extra rows
+        // 0: no extra rows; 1: up to 32, one block row shared by the two wavefront rows (each takes
+        // half of its column blocks: 1/8 more MFMAs); 2: up to 64, a block row per wavefront row (1/4 more)
+        constexpr int kExtMode = decltype(ext_tag)::value;
+        constexpr bool kExt = kExtMode > 0, kHalf = kExtMode == 1;
+        using half_tag = std::integral_constant<bool, kHalf>;
         constexpr int kMfma = kAct * Cfg::kBlkN, kReads = kAct ? kAct + Cfg::kBlkN : 0;
         if constexpr (kExt) {
 #pragma unroll
@@ -591,10 +611,10 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
                 for (int r = 0; r < 16; ++r)
                     accx[j][r] = 0.0f;
             if constexpr (kGather) { // the extra rows of this tile: looked up here, a round trip per tall tile
-                gather_lookup_x(cur, cur_xrow);
+                gather_lookup_x(cur, cur_xrow, kHalf);
                 gather_offset_x(cur_xrow);
             }
-            load_x_first();
+            load_x_first(kHalf);
         }
 #pragma unroll
         for (int i = 0; i < Cfg::kBlkM; ++i)
@@ -613,7 +633,7 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
             read_frags(u, ks + 1, (ks + 1) & 1, act);
             mfma_all(ks & 1, act);
             if constexpr (kExt)
-                mfma_x(ks & 1, ks_tag, kt + 1);
+                mfma_x(ks & 1, ks_tag, kt + 1, half_tag{});
             interleave_under_mfma<kMfma, kReads, loads_at(ks + 1)>();
         };
         // The body is branch free (a branch around the LDS reads would make the compiler wait for
@@ -632,7 +652,7 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
             read_frags(unit_a(u, 1), 0, 0, act); // past the last K tile: the next output tile's, read again there
             mfma_all((kKSteps - 1) & 1, act);
             if constexpr (kExt)
-                mfma_x((kKSteps - 1) & 1, std::integral_constant<int, kKSteps - 1>{}, kt + 1);
+                mfma_x((kKSteps - 1) & 1, std::integral_constant<int, kKSteps - 1>{}, kt + 1, half_tag{});
             interleave_under_mfma<kMfma, kReads, loads_at(0)>();
             u = unit_a(u, 1);
         };
@@ -728,7 +748,32 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
             // the matrix pipe may be read by the vector ALU 18 wait states after the instruction at
             // the earliest; the last one was issued before the block rows above were stored
             asm volatile("s_nop 15\n\ts_nop 3" : "+v"(accx[0]), "+v"(accx[1]), "+v"(accx[Cfg::kBlkN - 2]), "+v"(accx[Cfg::kBlkN - 1]));
-            store_row((int64_t)cur.m0 + BM + wm * 32 + m_lane, accx, std::false_type{});
+            if constexpr (!kHalf) {
+                store_row((int64_t)cur.m0 + BM + wm * 32 + m_lane, accx, std::false_type{});
+            } else {
+                // accx[jj] is column block wm + 2 jj of this wavefront column
+                const int64_t m = (int64_t)cur.m0 + BM + m_lane;
+                if (m < cur.m_end) {
+                    uint16_t *crow = C + m * Ndim;
+#pragma unroll
+                    for (int jo = 0; jo < (kSwiglu ? 1 : Cfg::kBlkN / 2); ++jo) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int col = cur.n0 + wn * (kOutBlkN * 32) + (wm + 2 * jo) * 32 + q * 8 + n_lane;
+                            if (col >= Ndim)
+                                continue;
+                            float v[4];
+#pragma unroll
+                            for (int t = 0; t < 4; ++t)
+                                v[t] = kSwiglu ? silu_mul(accx[0][q * 4 + t], accx[1][q * 4 + t]) : accx[jo][q * 4 + t];
+                            u32x2 o;
+                            o[0] = pack_bf16x2(v[0], v[1]);
+                            o[1] = pack_bf16x2(v[2], v[3]);
+                            *reinterpret_cast<u32x2 *>(crow + col) = o;
+                        }
+                    }
+                }
+            }
         }
     };
 
@@ -769,11 +814,14 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         // rows of the segment inside this wavefront's part of the tile -> active 32-row blocks
         const int64_t rows = (int64_t)cur.m_end - ((int64_t)cur.m0 + wm * Cfg::kWaveM);
         const int active = rows <= 0 ? 0 : (rows >= Cfg::kWaveM ? Cfg::kBlkM : (int)((rows + 31) / 32));
-        using ext_no = std::false_type;
-        using ext_yes = std::integral_constant<bool, kTall>;
+        using ext_no = std::integral_constant<int, 0>;
+        using ext_half = std::integral_constant<int, kTall ? 1 : 0>;
+        using ext_full = std::integral_constant<int, kTall ? 2 : 0>;
         if (active == Cfg::kBlkM) {
-            if (kTall && cur.ext > 0)
-                run_tile(std::integral_constant<int, Cfg::kBlkM>{}, ext_yes{});
+            if (kTall && cur.ext > 32)
+                run_tile(std::integral_constant<int, Cfg::kBlkM>{}, ext_full{});
+            else if (kTall && cur.ext > 0)
+                run_tile(std::integral_constant<int, Cfg::kBlkM>{}, ext_half{});
             else
                 run_tile(std::integral_constant<int, Cfg::kBlkM>{}, ext_no{});
         } else if (active == 0)
