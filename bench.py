@@ -103,11 +103,13 @@ class Layer:
             c = mi.recv_segment_counts(cfg, R, 0)
             seg = np.concatenate([[0], np.cumsum(c)]).astype(np.int32)
             self.recv_seg = mid.to_device(seg)
+        self.sums = None if self.ep else torch.empty((N, H), dtype=torch.float32, device=dev)
         self.names = ["route", "layout", "permute", "ffn_schedule", "ffn_gate_up", "ffn_down", "combine"]
 
-    def step(self, i, events=None, fused_gather=False):
+    def step(self, i, events=None, fused_gather=False, fused_combine=False):
         """One pass of the layer.  fused_gather (single-device layers only): no permute; the gate/up GEMM
-        fetches its rows from x through row_of_slot."""
+        fetches its rows from x through row_of_slot.  fused_combine: no y and no combine step; the down
+        GEMM adds its gate-weighted rows into the tokens' fp32 sums."""
         hub, cfg = self.hub, self.cfg
         s = self.sets[i % len(self.sets)]
         rec = (lambda j: events[j].record()) if events is not None else (lambda j: None)
@@ -131,9 +133,13 @@ class Layer:
         else:
             hub.moe_ffn_gate_up(ffn_in, seg, self.W_gate, self.W_up, s["ffn_ws"])
         rec(5)
-        hub.moe_ffn_down(seg, self.W_down, s["y"], s["ffn_ws"])
-        rec(6)
-        hub.moe_combine(s["y"], cfg.K, s["slot"], s["w"], s["out"])
+        if fused_combine:
+            hub.moe_ffn_down_combine(cfg.K, seg, self.W_down, s["row"], s["w"], self.sums, s["out"], s["ffn_ws"])
+            rec(6)
+        else:
+            hub.moe_ffn_down(seg, self.W_down, s["y"], s["ffn_ws"])
+            rec(6)
+            hub.moe_combine(s["y"], cfg.K, s["slot"], s["w"], s["out"])
         rec(7)
 
 
@@ -287,6 +293,21 @@ def main():
         f_gu = sum(e[4].elapsed_time(e[5]) for e in evf) * 1e3 / args.steps
         result["fused_gather"] = {"ms_per_step": f_ms, "tokens_per_s": N / (f_ms * 1e-3), "gate_up_us": f_gu,
                                   "tflops_gate_up": flops_gu / (f_gu * 1e-6) / 1e12}
+        # Both halves fused (no permute, no y, no combine step): the layer without data-shuffling steps.
+        if cfg.dtype == mi.BF16:
+            for i in range(min(3, args.warmup)):
+                layer.step(i, fused_gather=True, fused_combine=True)
+            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(args.steps)]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(args.steps):
+                layer.step(i, evs[i], fused_gather=True, fused_combine=True)
+            torch.cuda.synchronize()
+            s_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+            s_dn = sum(e[5].elapsed_time(e[6]) for e in evs) * 1e3 / args.steps
+            result["fused_gather_and_combine"] = {
+                "ms_per_step": s_ms, "tokens_per_s": N / (s_ms * 1e-3), "down_and_combine_us": s_dn,
+                "down_plus_combine_us_unfused": us["ffn_down"] + us["combine"]}
     if args.graph:
         # The same steps captured once and replayed: what a serving loop would do with a launch-bound layer.
         # Every replay is checked against the eager result (the kernels are deterministic, so bit for bit).

@@ -201,6 +201,24 @@ int moe_ffn_down(int dtype, int64_t M, int64_t H, int64_t F,
                  void *y, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * GEMM2 with the combine folded into its epilogue: the other half of a layer without data-
+ * shuffling steps (Section III-A, Section VI-B), for a single device that computes all experts.
+ * y is neither written nor read.  For every slot m with flat row r = row_of_slot[m] = n*K + k,
+ *   sums[n, :] += topk_w[n, k] * (a[m, :] W_down[e(m)]^T)
+ * is added with fp32 atomic adds to `sums` [N,H] fp32 (caller's scratch, cleared by the call), and
+ * out[n, :] is sums[n, :] rounded once to dtype.  moe_ffn_schedule (with M = N*K) and a GEMM1 go
+ * before it as they go before moe_ffn_down.  The K additions of an element happen in the order
+ * the workgroups reach them, so, unlike moe_ffn_down + moe_combine (ascending k), the result is
+ * not bit-reproducible from run to run (fp32 addition order; the products are not rounded to
+ * bf16 first, so it is the closer of the two to the exact sum).
+ * MOE_BF16 only.  sums and out 16-byte aligned; H a multiple of 8.
+ */
+int moe_ffn_down_combine(int dtype, int64_t N, int K, int64_t H, int64_t F, int E_local,
+                         const int32_t *seg_offsets, const void *W_down,
+                         const int32_t *row_of_slot, const float *topk_w, float *sums,
+                         void *out, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Combine and scaling (Section II-A, steps 4-5): rows return to their tokens
  * and are summed with the routing weights,
  *   out[n,:] = sum_{k=0..K-1} topk_w[n,k] * y[slot_of_row[n*K+k], :]

@@ -34,6 +34,8 @@ _SIGNATURES = {
                                  _c_vp, _c_sz, _c_vp]),
     "moe_ffn_gate_up_gather": (_c_int, [_c_vp, _c_int, _c_i64, _c_int, _c_i64, _c_i64, _c_int, _c_vp, _c_vp,
                                         _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
+    "moe_ffn_down_combine": (_c_int, [_c_int, _c_i64, _c_int, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp, _c_vp,
+                                      _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
     "moe_ffn_down": (_c_int, [_c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
     "moe_combine": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp, _c_vp]),
 }
@@ -225,6 +227,22 @@ def moe_ffn_down(seg_offsets, W_down, y, ws):
     wp, wb = _ws_args(ws)
     _check(load_library().moe_ffn_down(_dtype_code(y), M, H, F, E_local, _ptr(seg_offsets), _ptr(W_down),
                                        _ptr(y), wp, wb, _stream()))
+
+
+def moe_ffn_down_combine(K: int, seg_offsets, W_down, row_of_slot, topk_w, sums, out, ws):
+    import torch
+    N, H = out.shape
+    E_local, H2, F = W_down.shape
+    assert H2 == H and out.is_contiguous() and W_down.is_contiguous() and W_down.dtype == out.dtype
+    assert seg_offsets.numel() == E_local + 1
+    _need(row_of_slot, torch.int32, "row_of_slot")
+    _need(topk_w, torch.float32, "topk_w")
+    _need(sums, torch.float32, "sums")
+    assert row_of_slot.numel() == N * K and topk_w.numel() == N * K and sums.numel() == N * H
+    wp, wb = _ws_args(ws)
+    _check(load_library().moe_ffn_down_combine(_dtype_code(out), N, K, H, F, E_local, _ptr(seg_offsets),
+                                               _ptr(W_down), _ptr(row_of_slot), _ptr(topk_w), _ptr(sums),
+                                               _ptr(out), wp, wb, _stream()))
 
 
 def moe_combine(y, K: int, slot_of_row, topk_w, out):

@@ -299,6 +299,32 @@ extern "C" int moe_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_lo
                            static_cast<hipStream_t>(stream));
 }
 
+extern "C" int moe_ffn_down_combine(int dtype, int64_t N, int K, int64_t H, int64_t F, int E_local,
+                                    const int32_t *seg_offsets, const void *W_down,
+                                    const int32_t *row_of_slot, const float *topk_w, float *sums,
+                                    void *out, void *ws, size_t ws_bytes, void *stream)
+{
+    clear_error();
+    if (N < 0 || K < 1 || K > MOE_MAX_TOPK || N * (int64_t)K >= ((int64_t)1 << 31))
+        return fail(MOE_ERR_ARG, "N >= 0, 1 <= K <= %d and N*K < 2^31 are required (got N=%lld, K=%d)",
+                    MOE_MAX_TOPK, (long long)N, K);
+    const int64_t M = N * (int64_t)K;
+    MOE_TRY(check_ffn_common(dtype, M, H, F, E_local, seg_offsets, ws, ws_bytes));
+    if (dtype != MOE_BF16)
+        return fail(MOE_ERR_UNSUPPORTED, "moe_ffn_down_combine is built for MOE_BF16 only");
+    if (M == 0)
+        return MOE_OK;
+    MOE_NEED(W_down);
+    MOE_NEED(row_of_slot);
+    MOE_NEED(topk_w);
+    MOE_NEED(sums);
+    MOE_NEED(out);
+    if (!aligned16(sums) || !aligned16(out))
+        return fail(MOE_ERR_ARG, "sums and out must be 16-byte aligned");
+    return launch_ffn_down_combine(N, K, H, F, E_local, W_down, row_of_slot, topk_w, sums, out, ws,
+                                   static_cast<hipStream_t>(stream));
+}
+
 extern "C" int moe_grouped_ffn(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
                                int E_local, const int32_t *seg_offsets, const void *W_gate,
                                const void *W_up, const void *W_down, void *y, void *ws,

@@ -308,13 +308,14 @@ static int workgroup_slots(int per_cu)
     return g < kXcds ? kXcds : g;
 }
 
-template <class Main, class Light, bool kSwiglu, bool kGather = false>
+template <class Main, class Light, bool kSwiglu, bool kGather = false, bool kScatter = false>
 static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const uint16_t *B0,
                         const uint16_t *B1, uint16_t *C, TileTableHeader *hdr,
                         const TileEntry *table, int patch, hipStream_t st,
-                        const int32_t *gather_rows = nullptr, int gather_div = 1, uint32_t gather_bytes = 0)
+                        const int32_t *gather_rows = nullptr, int gather_div = 1, uint32_t gather_bytes = 0,
+                        const float *scatter_w = nullptr)
 {
-    auto kern = grouped_gemm_bf16<Main, Light, kSwiglu, kGather>;
+    auto kern = grouped_gemm_bf16<Main, Light, kSwiglu, kGather, kScatter>;
     size_t lds_bytes = Main::kLdsBytes;
     if constexpr (!std::is_void<Light>::value)
         lds_bytes = lds_bytes > Light::kLdsBytes ? lds_bytes : Light::kLdsBytes;
@@ -327,7 +328,7 @@ static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const 
     // persistent grid: the workgroups draw their tiles from the table's counters
     const int grid = workgroup_slots(Main::kLdsBytes <= 80 * 1024 ? 2 : 1);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(Main::kThreads), lds_bytes, st, A, M, Kdim, Ndim, B0, B1, C,
-                       hdr, table, patch, gather_rows, gather_div, gather_bytes);
+                       hdr, table, patch, gather_rows, gather_div, gather_bytes, scatter_w);
 }
 
 int check_ffn_shape(int dtype, int64_t H, int64_t F)
@@ -417,6 +418,49 @@ int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     uint16_t *yb = static_cast<uint16_t *>(y);
     launch_gemm<BigTile<false>, ShallowTile<false>, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, kPatch, st);
     return check_launch("moe_ffn_down");
+}
+
+// ------------------------------------------------------------------------
+// down projection with the combine in its epilogue
+// ------------------------------------------------------------------------
+__global__ void fill_zero_16B(u32x4 *__restrict__ p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        p[i] = u32x4{0u, 0u, 0u, 0u};
+}
+
+// sums[N*H] fp32 -> out[N*H] bf16, eight elements per thread
+__global__ void round_sums_bf16(const f32x4 *__restrict__ sums, u32x4 *__restrict__ out, int64_t n8)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n8)
+        return;
+    const f32x4 a = __builtin_nontemporal_load(&sums[2 * i]), b = __builtin_nontemporal_load(&sums[2 * i + 1]);
+    u32x4 o;
+    o[0] = pack_bf16x2(a[0], a[1]);
+    o[1] = pack_bf16x2(a[2], a[3]);
+    o[2] = pack_bf16x2(b[0], b[1]);
+    o[3] = pack_bf16x2(b[2], b[3]);
+    out[i] = o;
+}
+
+int launch_ffn_down_combine(int64_t N, int K, int64_t H, int64_t F, int E_local, const void *W_down,
+                            const int32_t *row_of_slot, const float *topk_w, float *sums, void *out,
+                            void *ws, hipStream_t st)
+{
+    const int64_t M = N * K;
+    const FfnPlan p = make_plan(M, H, F, E_local);
+    const FfnWorkspace k = carve(p, ws);
+    const int64_t n16 = N * H / 4, n8 = N * H / 8;
+    hipLaunchKernelGGL(fill_zero_16B, dim3((unsigned)ceil_div(n16, 256)), dim3(256), 0, st,
+                       reinterpret_cast<u32x4 *>(sums), n16);
+    launch_gemm<BigTile<false>, ShallowTile<false>, false, false, true>(
+        k.a, M, (int)F, (int)H, static_cast<const uint16_t *>(W_down), nullptr,
+        reinterpret_cast<uint16_t *>(sums), k.hdr2, k.tab2, kPatch, st, row_of_slot, K, 0u, topk_w);
+    hipLaunchKernelGGL(round_sums_bf16, dim3((unsigned)ceil_div(n8, 256)), dim3(256), 0, st,
+                       reinterpret_cast<const f32x4 *>(sums), static_cast<u32x4 *>(out), n8);
+    return check_launch("moe_ffn_down_combine");
 }
 
 }  // namespace moe

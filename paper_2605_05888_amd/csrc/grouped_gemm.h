@@ -224,14 +224,19 @@ struct GemmCfg {
 // or `void`.  Both geometries have the same workgroup size, BN and K tile.
 // kGather: row m of the A operand is row gather_rows[m] / gather_div of `A` (the dispatch's row
 // move done by the operand loads themselves) instead of row m.
-template <class Main, class Light, bool kSwiglu, bool kGather>
+// kScatter: the result is not stored as row m of C.  `C` is an fp32 matrix of Ndim columns, and row
+// m of the result, times scatter_w[gather_rows[m]], is added (atomically) to its row
+// gather_rows[m] / gather_div: the combine step done by the epilogue.
+template <class Main, class Light, bool kSwiglu, bool kGather, bool kScatter = false>
 __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 : 1)) void grouped_gemm_bf16(
     const uint16_t *__restrict__ A, int64_t M, int Kdim, int Ndim,
     const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
     uint16_t *__restrict__ C, TileTableHeader *__restrict__ hdr,
     const TileEntry *__restrict__ table, int patch,
-    const int32_t *__restrict__ gather_rows, int gather_div, uint32_t gather_bytes)
+    const int32_t *__restrict__ gather_rows, int gather_div, uint32_t gather_bytes,
+    const float *__restrict__ scatter_w)
 {
+    static_assert(!(kGather && kScatter) && !(kScatter && kSwiglu), "kScatter belongs to the down projection");
 #if defined(__HIP_DEVICE_COMPILE__) // the body uses device-only types (buffer resources); the host pass only needs the stub
     constexpr bool kTwo = !std::is_void<Light>::value;
     if constexpr (kTwo)
@@ -707,12 +712,41 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         // register of its own across the whole persistent loop
         asm volatile("" : "+v"(m_lane), "+v"(n_lane));
         constexpr int kOutBlkN = kSwiglu ? Cfg::kBlkN / 2 : Cfg::kBlkN;
-        // one 32-row block row of accumulators -> row m of C
+        // where row m of the result goes: row m of C, or (kScatter) its token's row of the fp32 sums
+        struct RowDst {
+            uint16_t *crow;
+            float *sums;
+            float w;
+        };
+        auto row_dst = [&](int64_t m) {
+            RowDst d = {nullptr, nullptr, 0.0f};
+            if constexpr (kScatter) {
+                const int32_t r = gather_rows[m];
+                d.w = scatter_w[r];
+                d.sums = reinterpret_cast<float *>(C) + (int64_t)(r / gather_div) * Ndim;
+            } else {
+                d.crow = C + m * Ndim;
+            }
+            return d;
+        };
+        auto put4 = [&](const RowDst &d, int col, const float (&v)[4]) {
+            if constexpr (kScatter) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    unsafeAtomicAdd(d.sums + col + t, d.w * v[t]);
+            } else {
+                u32x2 o;
+                o[0] = pack_bf16x2(v[0], v[1]);
+                o[1] = pack_bf16x2(v[2], v[3]);
+                *reinterpret_cast<u32x2 *>(d.crow + col) = o;
+            }
+        };
+        // one 32-row block row of accumulators -> row m of the result
         auto store_row = [&](int64_t m, const auto &blk, auto in_acc_regs) {
             constexpr bool kAccRegs = decltype(in_acc_regs)::value;
             if (m >= cur.m_end)
                 return;
-            uint16_t *crow = C + m * Ndim;
+            const RowDst dst = row_dst(m);
 #pragma unroll
             for (int j = 0; j < kOutBlkN; ++j) {
 #pragma unroll
@@ -730,10 +764,7 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
                         else
                             v[t] = kAccRegs ? acc_read(blk[j][r]) : blk[j][r];
                     }
-                    u32x2 o;
-                    o[0] = pack_bf16x2(v[0], v[1]);
-                    o[1] = pack_bf16x2(v[2], v[3]);
-                    *reinterpret_cast<u32x2 *>(crow + col) = o;
+                    put4(dst, col, v);
                 }
                 // one block at a time: left alone, the scheduler first copies the whole tile out of the
                 // accumulation registers and needs some two hundred registers to hold it
@@ -754,7 +785,7 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
                 // accx[jj] is column block wm + 2 jj of this wavefront column
                 const int64_t m = (int64_t)cur.m0 + BM + m_lane;
                 if (m < cur.m_end) {
-                    uint16_t *crow = C + m * Ndim;
+                    const RowDst dst = row_dst(m);
 #pragma unroll
                     for (int jo = 0; jo < (kSwiglu ? 1 : Cfg::kBlkN / 2); ++jo) {
 #pragma unroll
@@ -766,10 +797,7 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
 #pragma unroll
                             for (int t = 0; t < 4; ++t)
                                 v[t] = kSwiglu ? silu_mul(accx[0][q * 4 + t], accx[1][q * 4 + t]) : accx[jo][q * 4 + t];
-                            u32x2 o;
-                            o[0] = pack_bf16x2(v[0], v[1]);
-                            o[1] = pack_bf16x2(v[2], v[3]);
-                            *reinterpret_cast<u32x2 *>(crow + col) = o;
+                            put4(dst, col, v);
                         }
                     }
                 }

@@ -22,7 +22,8 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == {"moe_last_error", "moe_workspace_bytes", "moe_route", "moe_dispatch_layout",
                           "moe_dispatch_layout_arrival",
                           "moe_permute", "moe_grouped_ffn", "moe_combine",
-                          "moe_ffn_schedule", "moe_ffn_gate_up", "moe_ffn_gate_up_gather", "moe_ffn_down"}
+                          "moe_ffn_schedule", "moe_ffn_gate_up", "moe_ffn_gate_up_gather", "moe_ffn_down",
+                          "moe_ffn_down_combine"}
     lib = ctypes.CDLL(hub.lib_path()) if os.path.exists(hub.lib_path()) else hub.load_library()
     for n in names:
         assert hasattr(lib, n), n
@@ -72,6 +73,10 @@ ALIGNED = 0x1000   # a fake, well-aligned, never-dereferenced pointer: every cas
                                  None, 0, None), -3, "workspace"),
     (lambda L: L.moe_grouped_ffn(ALIGNED, hub.BF16, 64, 96, 64, 2, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED,
                                  ALIGNED, 1 << 30, None), -2, "multiples of 64"),
+    (lambda L: L.moe_ffn_down_combine(hub.F32, 4, 2, 64, 64, 2, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED,
+                                      ALIGNED, 1 << 30, None), -2, "BF16"),
+    (lambda L: L.moe_ffn_down_combine(hub.BF16, 4, 0, 64, 64, 2, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED,
+                                      ALIGNED, 1 << 30, None), -1, "K"),
     (lambda L: L.moe_combine(ALIGNED, hub.BF16, 4, 64, 0, ALIGNED, ALIGNED, ALIGNED, None), -1, "K"),
     (lambda L: L.moe_combine(ALIGNED, hub.F32, 4, 6, 2, ALIGNED, ALIGNED, ALIGNED, None), -1, "16"),
 ])

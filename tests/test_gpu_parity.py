@@ -347,6 +347,48 @@ def test_gate_up_with_fused_gather_equals_permute_then_gate_up(G, name):
     G.check_close(ys[1], o_y, *G.tolerances(cfg), what="y (fused gather)")
 
 
+@pytest.mark.parametrize("name", list(SMALL))
+def test_down_projection_with_combine_in_its_epilogue(G, name):
+    """GEMM2 adding gate-weighted rows straight into the tokens' sums (no y, no moe_combine): the additions
+    of an element come in no fixed order, so the comparison is by tolerance - against the oracle, and
+    against the GPU's own moe_ffn_down + moe_combine within a few bf16 steps."""
+    import moe_inputs.device as mid
+    import torch
+    import paper_2605_05888_amd as hub
+    cfg = SMALL[name]
+    if cfg.dtype != mi.BF16:
+        pytest.skip("bf16 only")
+    _say("down + combine fused", cfg)
+    x, Wr = mi.host_tensor(cfg, mi.STREAM_X), mi.host_tensor(cfg, mi.STREAM_W_ROUTER)
+    Wg, Wu, Wd = (mi.host_tensor(cfg, s) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    bias = mi.router_bias(cfg)
+    o_idx, o_w, _ = oracle.route(x, Wr, bias, cfg.K, cfg.score_mode)
+    o_lay = oracle.layout(o_idx, cfg.E, cfg.G)
+    o_y = oracle.ffn_rows(oracle.permute(x, cfg.K, o_lay["slot_of_row"]), o_lay["expert_offsets"], Wg, Wu, Wd)
+    o_out = oracle.combine(o_y, cfg.K, o_lay["slot_of_row"], o_w)
+    dx, dWg, dWu, dWd = (mid.to_device(t) for t in (x, Wg, Wu, Wd))
+    idx, w, _ = G.gpu_route(dx, mid.to_device(Wr), None if bias is None else mid.to_device(bias), cfg.K,
+                            cfg.score_mode, want_logits=False)
+    lay = G.gpu_layout(idx, cfg.E, cfg.G)
+    seg, R = lay["expert_offsets"], cfg.N * cfg.K
+    xp = G.gpu_permute(dx, cfg.K, lay)
+    ws = torch.zeros(hub.workspace_bytes(hub.OP_GROUPED_FFN, N=R, H=cfg.H, E=cfg.E, F=cfg.F, dtype=hub.BF16),
+                     dtype=torch.uint8, device="cuda:0")
+    hub.moe_ffn_schedule(hub.BF16, R, cfg.H, cfg.F, seg, ws)
+    hub.moe_ffn_gate_up(xp, seg, dWg, dWu, ws)
+    y = torch.zeros((R, cfg.H), dtype=torch.bfloat16, device="cuda:0")
+    hub.moe_ffn_down(seg, dWd, y, ws)
+    ref = G.host(G.gpu_combine(y, cfg.K, lay["slot_of_row"], w))
+    sums = torch.full((cfg.N, cfg.H), 7.0, dtype=torch.float32, device="cuda:0")       # the call clears it
+    for _ in range(2):                                                               # and may be repeated
+        out = torch.zeros((cfg.N, cfg.H), dtype=torch.bfloat16, device="cuda:0")
+        hub.moe_ffn_down_combine(cfg.K, seg, dWd, lay["row_of_slot"], w, sums, out, ws)
+        torch.cuda.synchronize()
+        got = G.host(out)
+        G.check_close(got, o_out, *G.tolerances(cfg), what="out (combine in the epilogue)")
+        G.check_close(got, G.as_f64(ref), 2e-2, 4e-3, what="against moe_ffn_down + moe_combine")
+
+
 def test_ffn_gemm_without_schedule_does_nothing(G):
     """A workspace no schedule was built in holds no tile table: the GEMM steps leave their outputs alone."""
     import moe_inputs.device as mid
