@@ -261,7 +261,8 @@ def test_ffn_remainder_rows_riding_with_the_last_full_tile(G):
     Wg, Wu, Wd = (mi.host_tensor(cfg, s) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
     dWg, dWu, dWd, dseg = (mid.to_device(t) for t in (Wg, Wu, Wd, seg))
     y = G.host(G.gpu_ffn(mid.to_device(xp), dseg, dWg, dWu, dWd))
-    G.check_close(y, oracle.ffn_rows(xp, seg, Wg, Wu, Wd), *G.tolerances(cfg), what="ffn with tall tiles")
+    o_y = oracle.ffn_rows(xp, seg, Wg, Wu, Wd)
+    G.check_close(y, o_y, *G.tolerances(cfg), what="ffn with tall tiles")
     # every segment reversed: the remainder rows are now computed as ordinary rows of a full tile
     rev = np.concatenate([np.arange(seg[e], seg[e + 1])[::-1] for e in range(E)]).astype(np.int32)
     y_rev = G.host(G.gpu_ffn(mid.to_device(np.ascontiguousarray(xp[rev])), dseg, dWg, dWu, dWd))
@@ -277,6 +278,17 @@ def test_ffn_remainder_rows_riding_with_the_last_full_tile(G):
     hub.moe_ffn_down(dseg, dWd, yg, ws)
     torch.cuda.synchronize()
     assert np.array_equal(G.host(yg), y)
+    # and through the down GEMM that adds its rows into the tokens' sums (K = 1: token r gets slot m's
+    # row times its weight, r = rev[m]), whose epilogue has its own code for the remainder rows
+    rng = np.random.default_rng(7)
+    w = (0.5 + rng.random(M)).astype(np.float32)
+    sums = torch.empty((M, cfg.H), dtype=torch.float32, device="cuda:0")
+    out = torch.zeros((M, cfg.H), dtype=dt, device="cuda:0")
+    hub.moe_ffn_down_combine(1, dseg, dWd, mid.to_device(rev), mid.to_device(w).reshape(M, 1), sums, out, ws)
+    torch.cuda.synchronize()
+    want = np.empty((M, cfg.H))
+    want[rev] = w[rev, None].astype(np.float64) * o_y
+    G.check_close(G.host(out), want, *G.tolerances(cfg), what="rows added into the sums")
 
 
 def test_ffn_steps_rerun_after_one_schedule(G):
