@@ -6,15 +6,20 @@ One "step" = one pass of the whole hot path over one batch of synthetic tokens:
     moe_ffn_gate_up -> moe_ffn_down -> moe_combine
 all enqueued on one stream through the C ABI, inputs resident in HBM.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mixtral]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload dsv3] [--also a,b,c | --also none]
+    python bench.py --sweep tokens      # Mixtral shape, 128 ... 32768 tokens
+    python bench.py --sweep imbalance   # Mixtral shape, std of the experts' token shares 0 ... 0.05
 
-Prints ONE JSON line: layer tokens/s, the roofline of the dominant kernel
-(the gate/up grouped GEMM, timed live with HIP events), the HBM rate of the
-permute and combine row moves, and the CPU oracle timed on a bounded sample.
+Prints ONE JSON line.  Its top level is the main workload (by default the largest
+single-GPU configuration, the DeepSeek-V3-shaped layer over all 256 experts): layer
+tokens/s, the roofline of the dominant kernel (the gate/up grouped GEMM, timed live with
+HIP events), the HBM rate of the permute and combine row moves, and the CPU oracle timed on
+a bounded sample.  `also` holds the same measurements, in short, for the other workloads.
 """
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -31,26 +36,35 @@ WORKLOAD_TEXT = {
     "tiny": "Tiny MoE layer (fp32)",
     "mixtral": "Mixtral-8x7B-shaped layer",
     "gptoss": "gpt-oss-shaped layer, Zipf(1.0) expert popularity",
-    "dsv3": "DeepSeek-V3-shaped routed layer",
+    "dsv3": "DeepSeek-V3-shaped routed layer, FFN over all 256 experts",
     "dsv3_ep": "one expert-parallel rank's share of a DeepSeek-V3-shaped layer (32 destinations, 8 local experts)",
     "qwen2moe": "Qwen2-MoE-2.7B-shaped layer (paper Table II)",
     "phi35moe": "Phi-3.5-MoE-shaped layer (paper Table II)",
 }
+DEFAULT_WORKLOAD = "dsv3"
+DEFAULT_ALSO = "mixtral,gptoss,dsv3_ep,qwen2moe,phi35moe"
+SWEEP_TOKENS = [128, 256, 512, 1024, 2048, 4096, 8192, 16384, 32768]
+SWEEP_SHARE_STD = [0.0, 0.01, 0.02, 0.032, 0.04, 0.05]
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="mixtral", choices=list(WORKLOAD_TEXT))
-    ap.add_argument("--tokens", type=int, default=0, help="override the workload's token count (token-count sweeps)")
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=list(WORKLOAD_TEXT))
+    ap.add_argument("--also", default=None,
+                    help="comma-separated workloads measured in short beside the main one ('none': no others; "
+                         f"default: {DEFAULT_ALSO} when the main workload is {DEFAULT_WORKLOAD})")
+    ap.add_argument("--sweep", default=None, choices=["tokens", "imbalance"],
+                    help="emit a whole curve on the Mixtral shape under the key 'sweep' instead of 'also'")
+    ap.add_argument("--tokens", type=int, default=0, help="override the workload's token count")
     ap.add_argument("--zipf", type=float, default=-1.0,
-                    help="override the Zipf exponent of expert popularity (imbalance sweeps; 0 = uniform)")
+                    help="override the Zipf exponent of expert popularity (0 = uniform)")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a HIP graph (one graph of all buffer sets' steps)")
     ap.add_argument("--nbuf", type=int, default=0, help="activation buffer sets rotated per step (0 = auto)")
-    ap.add_argument("--cpu-seconds", type=float, default=18.0, help="target CPU time of the oracle sample (0 = skip)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target time of the oracle sample (0 = skip)")
     return ap.parse_args()
 
 
@@ -103,8 +117,12 @@ class Layer:
             c = mi.recv_segment_counts(cfg, R, 0)
             seg = np.concatenate([[0], np.cumsum(c)]).astype(np.int32)
             self.recv_seg = mid.to_device(seg)
-        self.sums = None if self.ep else torch.empty((N, H), dtype=torch.float32, device=dev)
+        self.sums = None
         self.names = ["route", "layout", "permute", "ffn_schedule", "ffn_gate_up", "ffn_down", "combine"]
+
+    def set_bias(self, bias):
+        import moe_inputs.device as mid
+        self.bias = None if bias is None else mid.to_device(bias)
 
     def step(self, i, events=None, fused_gather=False, fused_combine=False):
         """One pass of the layer.  fused_gather (single-device layers only): no permute; the gate/up GEMM
@@ -134,6 +152,8 @@ class Layer:
             hub.moe_ffn_gate_up(ffn_in, seg, self.W_gate, self.W_up, s["ffn_ws"])
         rec(5)
         if fused_combine:
+            if self.sums is None:
+                self.sums = self.torch.empty((cfg.N, cfg.H), dtype=self.torch.float32, device="cuda:0")
             hub.moe_ffn_down_combine(cfg.K, seg, self.W_down, s["row"], s["w"], self.sums, s["out"], s["ffn_ws"])
             rec(6)
         else:
@@ -144,8 +164,10 @@ class Layer:
 
 
 def cpu_baseline(cfg, layer, target_seconds):
-    """The oracle, as it stands, on a bounded sample of the same workload: a mini-batch of S
-    tokens through the whole layer (all experts, full H and F).  tokens/s = S / elapsed."""
+    """The oracle, as it stands, on a bounded sample of the same workload: a mini-batch of S tokens
+    through the whole layer (every expert the sample's rows reach, full H and F).  tokens/s = S / time
+    spent inside the oracle.  Expert weights are copied back from HBM one expert at a time, outside the
+    timed parts (the layer's weights need not fit host memory twice)."""
     import numpy as np
     import moe_inputs as mi
     import moe_inputs.device as mid
@@ -153,7 +175,6 @@ def cpu_baseline(cfg, layer, target_seconds):
     Wr = mid.to_host(layer.W_r)
     bias = None if layer.bias is None else mid.to_host(layer.bias)
     E_run = layer.E_local if layer.ep else cfg.E
-    Wg, Wu, Wd = mid.to_host(layer.W_gate), mid.to_host(layer.W_up), mid.to_host(layer.W_down)
     x_all = mid.to_host(layer.sets[0]["x"])
 
     def run(S):
@@ -162,34 +183,148 @@ def cpu_baseline(cfg, layer, target_seconds):
         idx, w, _ = oracle.route(x, Wr, bias, cfg.K, cfg.score_mode)
         lay = oracle.layout(idx, cfg.E, cfg.G)
         xp = oracle.permute(x, cfg.K, lay["slot_of_row"])
+        spent = time.perf_counter() - t0
         if layer.ep:   # the local experts see S*K received rows, split as in the GPU run
             c = mi.recv_segment_counts(cfg, S * cfg.K, 0)
             seg = np.concatenate([[0], np.cumsum(c)]).astype(np.int32)
         else:
             seg = lay["expert_offsets"]
-        y = oracle.ffn_rows(xp, seg, Wg[:E_run], Wu[:E_run], Wd[:E_run])
+        y = np.zeros((S * cfg.K, cfg.H), dtype=np.float64)
+        for e in range(E_run):
+            lo, hi = int(seg[e]), int(seg[e + 1])
+            if hi == lo:
+                continue
+            We = [mid.to_host(W[e:e + 1]) for W in (layer.W_gate, layer.W_up, layer.W_down)]
+            t0 = time.perf_counter()
+            y[lo:hi] = oracle.ffn_rows(xp, np.array([lo, hi], np.int32), *We, rows=np.arange(lo, hi))
+            spent += time.perf_counter() - t0
+        t0 = time.perf_counter()
         oracle.combine(y, cfg.K, lay["slot_of_row"], w)
-        return time.perf_counter() - t0
+        return spent + time.perf_counter() - t0
 
-    S = min(cfg.N, 16)
+    # first a sample large enough for every expert's rows to occupy the host's threads, then one scaled
+    # to the target time
+    S = int(min(cfg.N, max(16, 16 * E_run // cfg.K)))
     t = run(S)
-    S2 = int(max(S, min(cfg.N, S * target_seconds / max(t, 1e-3))))
-    if S2 > S:
+    S2 = int(min(cfg.N, S * target_seconds / max(t, 1e-3)))
+    if S2 > S * 1.5:
         S, t = S2, run(S2)
     return {"value": S / t, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"{S} of {cfg.N} tokens through the whole layer (route, layout, permute, fp64 SwiGLU FFN "
-                      f"over all {E_run} experts at full H and F, combine); {t:.1f} s of CPU time"}
+                      f"over the {E_run} experts at full H and F, combine); {t:.1f} s of wall time inside the "
+                      f"oracle on {oracle.num_threads()} threads"}
 
 
-def measured_traffic(workload, kernel):
-    """HBM bytes per launch from the committed rocprofv3 counter summaries (profiles/*_hbm_traffic.md), or None."""
+def profiled_traffic(workload, kernel):
+    """HBM bytes per launch as read from rocprofv3 counters in an earlier, committed run
+    (profiles/*_hbm_traffic.md); not measured by this run.  None if there is no such summary."""
     import glob
-    for path in glob.glob(os.path.join(ROOT, "profiles", "*_hbm_traffic.md")):
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*_hbm_traffic.md"))):
         for line in open(path):
             t = line.split()
             if len(t) == 4 and t[0] == "traffic_bytes" and t[1] == workload and t[2] == kernel:
-                return float(t[3])
-    return None
+                return float(t[3]), os.path.relpath(path, ROOT)
+    return None, None
+
+
+def time_layer(layer, steps, warmup, **variant):
+    """ms per step from the host clock around `steps` steps, and the mean HIP-event time of every call."""
+    import torch
+    for i in range(warmup):
+        layer.step(i, **variant)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        layer.step(i, ev[i], **variant)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    us = {n: sum(e[j].elapsed_time(e[j + 1]) for e in ev) * 1e3 / steps for j, n in enumerate(layer.names)}
+    return ms, us
+
+
+def summarise(cfg, layer, ms_per_step, us):
+    """The figures every workload reports."""
+    import moe_inputs as mi
+    N, H, K, F = cfg.N, cfg.H, cfg.K, cfg.F
+    R, b = N * K, cfg.elt_bytes
+    flops_gu, flops_dn = 4.0 * R * H * F, 2.0 * R * H * F      # gate and up projections; down projection
+    t_gu, t_dn = us["ffn_gate_up"] * 1e-6, us["ffn_down"] * 1e-6
+    move_bytes = N * H * b + R * H * b          # permute: read x once, write xp; combine: the mirror image
+    gbs_perm = (move_bytes + 4 * R) / (us["permute"] * 1e-6) / 1e9
+    gbs_comb = (move_bytes + 8 * R) / (us["combine"] * 1e-6) / 1e9
+    cnt = layer.sets[0]["cnt"].cpu().numpy().astype("float64")
+    return {
+        "ms_per_step": ms_per_step, "tokens_per_s": N / (ms_per_step * 1e-3),
+        "gate_up_tflops": flops_gu / t_gu / 1e12, "gate_up_mfma_frac": flops_gu / t_gu / 1e12 / PEAK_BF16_TFLOPS,
+        "down_tflops": flops_dn / t_dn / 1e12, "down_mfma_frac": flops_dn / t_dn / 1e12 / PEAK_BF16_TFLOPS,
+        "ffn_mfma_frac": (flops_gu + flops_dn) / (t_gu + t_dn) / 1e12 / PEAK_BF16_TFLOPS,
+        "permute_GBs": gbs_perm, "permute_hbm_frac": gbs_perm / PEAK_HBM_GBS,
+        "combine_GBs": gbs_comb, "combine_hbm_frac": gbs_comb / PEAK_HBM_GBS,
+        "step_breakdown_us": us,
+        "routing": {"zipf_s": cfg.zipf_s, "rows_per_expert_min": int(cnt.min()), "rows_per_expert_max": int(cnt.max()),
+                    "std_of_expert_share": float((cnt / max(cnt.sum(), 1.0)).std())},
+        "dtype": "bf16" if cfg.dtype == mi.BF16 else "f32",
+    }
+
+
+def pick_nbuf(cfg, nbuf_arg):
+    N, H, K, F, b = cfg.N, cfg.H, cfg.K, cfg.F, cfg.elt_bytes
+    act_bytes = (2 * N * H + 2 * N * K * H + N * K * F) * b
+    return nbuf_arg or (4 if act_bytes < (1 << 30) else 1)   # rotate small working sets out of the 256 MB cache
+
+
+def short_run(name, cfg, steps, warmup, nbuf_arg):
+    """One workload measured in short (the entries of `also` and of the sweeps)."""
+    import torch
+    nbuf = pick_nbuf(cfg, nbuf_arg)
+    layer = Layer(cfg, nbuf)
+    torch.cuda.synchronize()
+    ms, us = time_layer(layer, steps, warmup)
+    out = summarise(cfg, layer, ms, us)
+    out["config"] = {"workload": f"{name}: {WORKLOAD_TEXT.get(name, name)}", "N": cfg.N, "H": cfg.H, "E": cfg.E,
+                     "K": cfg.K, "F": cfg.F, "G": cfg.G, "activation_buffer_sets": nbuf}
+    del layer
+    torch.cuda.empty_cache()
+    return out
+
+
+def imbalance_point(base_cfg, target_std, steps, warmup, nbuf_arg):
+    """Mixtral shape with the experts' logits biased along a fixed seeded pattern; the gain of the bias is
+    searched (bisection over route + layout on the GPU) until the realised standard deviation of the
+    experts' token shares is the target."""
+    import torch
+    import moe_inputs as mi
+    nbuf = pick_nbuf(base_cfg, nbuf_arg)
+    layer = Layer(base_cfg, nbuf)
+
+    def realised(gain):
+        cfg = dataclasses.replace(base_cfg, bias_gain=gain)
+        layer.set_bias(mi.router_bias(cfg))
+        layer.step(0)
+        torch.cuda.synchronize()
+        cnt = layer.sets[0]["cnt"].cpu().numpy().astype("float64")
+        return float((cnt / cnt.sum()).std())
+
+    lo, hi = 0.0, 4.0
+    gain = 0.0
+    if target_std > 0:
+        for _ in range(24):
+            gain = 0.5 * (lo + hi)
+            if realised(gain) < target_std:
+                lo = gain
+            else:
+                hi = gain
+    got = realised(gain)
+    cfg = dataclasses.replace(base_cfg, bias_gain=gain)
+    ms, us = time_layer(layer, steps, warmup)
+    out = summarise(cfg, layer, ms, us)
+    out["target_std_of_expert_share"] = target_std
+    out["bias_gain"] = gain
+    assert abs(out["routing"]["std_of_expert_share"] - got) < 1e-9
+    del layer
+    torch.cuda.empty_cache()
+    return out
 
 
 def main():
@@ -205,54 +340,39 @@ def main():
     hub.load_library(build_if_missing=False)     # fail loudly if the HIP library is not built
     cfg = mi.CONFIGS[args.workload]
     if args.tokens > 0:
-        import dataclasses
         cfg = dataclasses.replace(cfg, N=args.tokens)
     if args.zipf >= 0:
-        import dataclasses
         cfg = dataclasses.replace(cfg, zipf_s=args.zipf)
     N, H, E, K, F, G = cfg.N, cfg.H, cfg.E, cfg.K, cfg.F, cfg.G
-    R, b = N * K, cfg.elt_bytes
-    act_bytes = (2 * N * H + 2 * R * H + R * F) * b
-    nbuf = args.nbuf or (4 if act_bytes < (1 << 30) else 1)   # rotate small working sets out of the 256 MB cache
+    R = N * K
+    nbuf = pick_nbuf(cfg, args.nbuf)
     layer = Layer(cfg, nbuf)
     torch.cuda.synchronize()
 
-    for i in range(args.warmup):
-        layer.step(i)
-    torch.cuda.synchronize()
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        layer.step(i, ev[i])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    us = {n: sum(e[j].elapsed_time(e[j + 1]) for e in ev) * 1e3 / args.steps for j, n in enumerate(layer.names)}
-
-    flops_gu = 4.0 * R * H * F                  # gate and up projections: 2 * (2*R*H*F)
-    flops_dn = 2.0 * R * H * F
-    t_gu, t_dn = us["ffn_gate_up"] * 1e-6, us["ffn_down"] * 1e-6
-    ach = flops_gu / t_gu / 1e12
-    move_bytes = N * H * b + R * H * b          # permute: read x once, write xp; combine: the mirror image
-    gbs_perm = (move_bytes + 4 * R) / (us["permute"] * 1e-6) / 1e9
-    gbs_comb = (move_bytes + 8 * R) / (us["combine"] * 1e-6) / 1e9
+    ms_per_step, us = time_layer(layer, args.steps, args.warmup)
+    m = summarise(cfg, layer, ms_per_step, us)
+    flops_gu = 4.0 * R * H * F
+    t_gu = us["ffn_gate_up"] * 1e-6
+    traffic, traffic_src = profiled_traffic(args.workload, "ffn_gate_up")
     result = {
-        "metric": "moe_layer_tokens_per_s", "value": N / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "metric": "moe_layer_tokens_per_s", "value": m["tokens_per_s"], "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if cfg.dtype == mi.BF16 else "f32", "data": "synthetic",
+        "dtype": m["dtype"], "data": "synthetic",
         "config": {"workload": f"{args.workload}: {WORKLOAD_TEXT[args.workload]}", "N": N, "H": H, "E": E, "K": K,
-                   "F": F, "G": G, "routed_rows": R, "activation_buffer_sets": nbuf},
+                   "F": F, "G": G, "routed_rows": R, "activation_buffer_sets": nbuf, "routing": m["routing"]},
         "roofline": {"kernel": "grouped_gemm_bf16 (gate/up projection with fused SwiGLU)", "bound": "mfma",
-                     "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
-                     "flops_per_launch": flops_gu, "avg_launch_us": us["ffn_gate_up"],
-                     "traffic": measured_traffic(args.workload, "ffn_gate_up")},
-        "ffn": {"tflops_gate_up": ach, "tflops_down": flops_dn / t_dn / 1e12,
-                "tflops_both": (flops_gu + flops_dn) / (t_gu + t_dn) / 1e12,
-                "mfma_frac_both": (flops_gu + flops_dn) / (t_gu + t_dn) / 1e12 / PEAK_BF16_TFLOPS},
-        "dispatch_combine": {"permute_GBs": gbs_perm, "combine_GBs": gbs_comb, "peak_GBs": PEAK_HBM_GBS,
-                             "permute_frac": gbs_perm / PEAK_HBM_GBS, "combine_frac": gbs_comb / PEAK_HBM_GBS},
+                     "achieved": m["gate_up_tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": m["gate_up_mfma_frac"], "flops_per_launch": flops_gu,
+                     "avg_launch_us": us["ffn_gate_up"],
+                     # bytes per launch from rocprofv3 counters of an earlier run of this command (see the file)
+                     "traffic": traffic, "traffic_from_committed_profile": traffic_src},
+        "ffn": {"tflops_gate_up": m["gate_up_tflops"], "tflops_down": m["down_tflops"],
+                "mfma_frac_gate_up": m["gate_up_mfma_frac"], "mfma_frac_down": m["down_mfma_frac"],
+                "mfma_frac_both": m["ffn_mfma_frac"]},
+        "dispatch_combine": {"permute_GBs": m["permute_GBs"], "combine_GBs": m["combine_GBs"],
+                             "peak_GBs": PEAK_HBM_GBS, "permute_frac": m["permute_hbm_frac"],
+                             "combine_frac": m["combine_hbm_frac"]},
         "step_breakdown_us": us,
     }
     # Address resolution alone, stable order against arrival order (atomic row pointers), same inputs.
@@ -281,36 +401,24 @@ def main():
     if not layer.ep:
         # Variant without a dispatch row move (a single device that computes every expert needs no send
         # buffer): the gate/up GEMM gathers its rows from x.  Reported beside the layer, not as `value`.
-        for i in range(min(3, args.warmup)):
-            layer.step(i, fused_gather=True)
-        evf = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(args.steps)]
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(args.steps):
-            layer.step(i, evf[i], fused_gather=True)
-        torch.cuda.synchronize()
-        f_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-        f_gu = sum(e[4].elapsed_time(e[5]) for e in evf) * 1e3 / args.steps
-        result["fused_gather"] = {"ms_per_step": f_ms, "tokens_per_s": N / (f_ms * 1e-3), "gate_up_us": f_gu,
-                                  "tflops_gate_up": flops_gu / (f_gu * 1e-6) / 1e12}
+        f_ms, f_us = time_layer(layer, args.steps, min(3, args.warmup), fused_gather=True)
+        result["fused_gather"] = {"ms_per_step": f_ms, "tokens_per_s": N / (f_ms * 1e-3),
+                                  "gate_up_us": f_us["ffn_gate_up"],
+                                  "tflops_gate_up": flops_gu / (f_us["ffn_gate_up"] * 1e-6) / 1e12}
         # Both halves fused (no permute, no y, no combine step): the layer without data-shuffling steps.
         if cfg.dtype == mi.BF16:
-            for i in range(min(3, args.warmup)):
-                layer.step(i, fused_gather=True, fused_combine=True)
-            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(args.steps)]
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for i in range(args.steps):
-                layer.step(i, evs[i], fused_gather=True, fused_combine=True)
-            torch.cuda.synchronize()
-            s_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-            s_dn = sum(e[5].elapsed_time(e[6]) for e in evs) * 1e3 / args.steps
+            n_fc = max(2, args.steps // 5)          # (an atomic per element: several times slower)
+            s_ms, s_us = time_layer(layer, n_fc, 1, fused_gather=True, fused_combine=True)
             result["fused_gather_and_combine"] = {
-                "ms_per_step": s_ms, "tokens_per_s": N / (s_ms * 1e-3), "down_and_combine_us": s_dn,
+                "ms_per_step": s_ms, "tokens_per_s": N / (s_ms * 1e-3), "steps": n_fc,
+                "down_and_combine_us": s_us["ffn_down"],
                 "down_plus_combine_us_unfused": us["ffn_down"] + us["combine"]}
+            layer.sums = None
     if args.graph:
         # The same steps captured once and replayed: what a serving loop would do with a launch-bound layer.
         # Every replay is checked against the eager result (the kernels are deterministic, so bit for bit).
+        for i in range(len(layer.sets)):
+            layer.step(i)
         eager_out = [st["out"].clone() for st in layer.sets]
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -339,11 +447,6 @@ def main():
         g_ms = (t1 - t0) * 1e3 / (reps * len(layer.sets))
         result["graph"] = {"ms_per_step": g_ms, "tokens_per_s": N / (g_ms * 1e-3), "steps_per_graph": len(layer.sets),
                            "replays_timed": reps, "matches_eager_bitwise": bool(same)}
-    # what the routing did: rows per expert, and the paper's imbalance measure (std of the experts' token shares)
-    cnt = layer.sets[0]["cnt"].cpu().numpy().astype("float64")
-    result["config"]["routing"] = {"zipf_s": cfg.zipf_s, "rows_per_expert_min": int(cnt.min()),
-                                   "rows_per_expert_max": int(cnt.max()),
-                                   "std_of_expert_share": float((cnt / max(cnt.sum(), 1.0)).std())}
     # achievable matrix rate of this box with this kernel: the gate/up GEMM over equal, tile-aligned segments
     M_even = (R // layer.E_local) // 256 * 256
     if M_even > 0 and cfg.dtype == mi.BF16:
@@ -377,6 +480,28 @@ def main():
     del src, dst
     if args.cpu_seconds > 0:
         result["cpu_baseline"] = cpu_baseline(cfg, layer, args.cpu_seconds)
+    del layer, st0
+    torch.cuda.empty_cache()
+
+    # ---- the other workloads, in short (same steps and warm-up, same measurements)
+    if args.sweep is None:
+        also = args.also
+        if also is None:
+            also = DEFAULT_ALSO if (args.workload == DEFAULT_WORKLOAD and args.tokens == 0 and args.zipf < 0) else "none"
+        names = [n for n in also.split(",") if n and n != "none" and n != args.workload]
+        if names:
+            result["also"] = {n: short_run(n, mi.CONFIGS[n], args.steps, args.warmup, args.nbuf) for n in names}
+    elif args.sweep == "tokens":
+        base = mi.CONFIGS["mixtral"]
+        result["sweep"] = {"what": "token count on the Mixtral shape (the axis of the paper's Fig. 13)", "points": [
+            dict(tokens=n, **short_run("mixtral", dataclasses.replace(base, N=n), args.steps, args.warmup, args.nbuf))
+            for n in SWEEP_TOKENS]}
+    else:
+        base = mi.CONFIGS["mixtral"]
+        result["sweep"] = {"what": "standard deviation of the experts' token shares on the Mixtral shape "
+                                   "(the axis of the paper's Fig. 14)",
+                           "points": [imbalance_point(base, s, args.steps, args.warmup, args.nbuf)
+                                      for s in SWEEP_SHARE_STD]}
     print(json.dumps(result))
 
 

@@ -19,11 +19,18 @@
  *    H * sizeof(element) (and F * sizeof(element)) a multiple of 16.
  *  - dtype is the storage type of activations and expert weights: MOE_BF16
  *    (fp32 accumulation) or MOE_F32.  Router weights and logits are fp32.
- *  - Return value: MOE_OK, or a negative error.  On error nothing has been
- *    launched and no output was touched; moe_last_error() describes it.
+ *  - Return value: MOE_OK, or a negative error; moe_last_error() describes it.
+ *    Every argument error (MOE_ERR_ARG, MOE_ERR_UNSUPPORTED, MOE_ERR_WORKSPACE)
+ *    is found before the first launch: nothing was enqueued and no output was
+ *    touched.  MOE_ERR_LAUNCH means the HIP runtime refused one of the call's
+ *    launches; earlier launches of the same call may already be enqueued.  A
+ *    HIP error that the caller's own earlier work left pending is cleared at
+ *    entry and never reported as this library's.
  *  - N == 0 (or M == 0) is a successful no-op.  Inputs must be finite.
- *  - No global mutable state: calls on different streams/threads are
- *    independent as long as their buffers are.
+ *  - The only state the library keeps between calls is a per-device cache of
+ *    device properties (compute-unit count, raised LDS limit), filled on first
+ *    use and safe to fill from several threads; calls on different streams or
+ *    threads are independent as long as their buffers are.
  */
 #ifndef MOE_HUB_H
 #define MOE_HUB_H
@@ -40,7 +47,8 @@ enum {
     MOE_ERR_ARG = -1,         /* null pointer, size out of range, misaligned row */
     MOE_ERR_UNSUPPORTED = -2, /* valid but not built (dtype, E too large, ...)    */
     MOE_ERR_WORKSPACE = -3,   /* workspace missing or smaller than required       */
-    MOE_ERR_LAUNCH = -4       /* the HIP runtime refused a launch                 */
+    MOE_ERR_LAUNCH = -4,      /* the HIP runtime refused a launch                 */
+    MOE_ERR_STATE = -5        /* moe_ffn_status: a GEMM step ran without a schedule */
 };
 
 enum { MOE_BF16 = 0, MOE_F32 = 1 };
@@ -134,6 +142,8 @@ int moe_dispatch_layout_arrival(const int32_t *topk_idx, int64_t N, int K, int E
  * expert-contiguous and therefore destination-contiguous: segment
  * [dest_offsets[g], dest_offsets[g+1]) is what would be sent to destination g.
  *   x [N,H] dtype     xp [N*K,H] dtype (out)
+ * Requires K <= 64 (MOE_ERR_UNSUPPORTED otherwise).  row_of_slot is accepted for
+ * symmetry with the layout's outputs and is not read.
  */
 int moe_permute(const void *x, int dtype, int64_t N, int64_t H, int K,
                 const int32_t *slot_of_row, const int32_t *row_of_slot,
@@ -170,8 +180,10 @@ int moe_grouped_ffn(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
  * device-side tile tables both GEMMs read; moe_ffn_gate_up leaves the activation
  * a[M,F] in the workspace; moe_ffn_down reads it and writes y.  The GEMM steps
  * may be launched again over the same schedule.  On a workspace that
- * moe_ffn_schedule has not filled for the same M (bf16) they find no tile table
- * and leave their outputs untouched; no error can be reported for that.
+ * moe_ffn_schedule has not filled for the same M (bf16) they find no tile table,
+ * leave their outputs untouched and set an error word in the workspace; the
+ * call itself still returns MOE_OK (it never waits for the device).
+ * moe_ffn_status reports that word.
  */
 int moe_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
                      const int32_t *seg_offsets, void *ws, size_t ws_bytes, void *stream);
@@ -180,9 +192,22 @@ int moe_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
                     const void *W_gate, const void *W_up,
                     void *ws, size_t ws_bytes, void *stream);
 /*
+ * Did every GEMM step launched over this workspace since the last moe_ffn_schedule
+ * find its schedule?  The one call of the library that waits: it synchronises
+ * `stream`, copies the workspace's two error words to the host and returns MOE_OK
+ * or MOE_ERR_STATE (a bf16 GEMM step ran over a workspace that moe_ffn_schedule had
+ * not filled for the same M, and wrote nothing).  For tests and debugging; the
+ * hot path does not need it.  fp32 workspaces have no schedule: always MOE_OK.
+ */
+int moe_ffn_status(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
+                   const void *ws, size_t ws_bytes, void *stream);
+/*
  * GEMM1 with the dispatch's row move folded into its operand loads: the paper's
- * ideal layer has no data-shuffling step between gating and the experts (Section
- * III-A; the "extra data manipulations" of Section VI-B are what it removes).  Row
+ * ideal MoE layer (Section II-C) runs routing, expert computation and scaling with
+ * no additional step in between; the extra handling of data that Section II-C
+ * counts among the scheduling overheads, and the shuffling of rows whose cost
+ * Section VI-B says grows with the sequence length, are what this variant removes
+ * on the dispatch side.  Row
  * m of the virtual xp is x[row_of_slot[m] / K, :], fetched where moe_ffn_gate_up
  * would fetch xp[m, :]; xp is neither written nor read.  The result, a[N*K,F] in
  * the workspace, is bit for bit that of moe_permute followed by moe_ffn_gate_up,
@@ -202,7 +227,7 @@ int moe_ffn_down(int dtype, int64_t M, int64_t H, int64_t F,
 
 /*
  * GEMM2 with the combine folded into its epilogue: the other half of a layer without data-
- * shuffling steps (Section III-A, Section VI-B), for a single device that computes all experts.
+ * shuffling steps (the ideal layer of Section II-C), for a single device that computes all experts.
  * y is neither written nor read.  For every slot m with flat row r = row_of_slot[m] = n*K + k,
  *   sums[n, :] += topk_w[n, k] * (a[m, :] W_down[e(m)]^T)
  * is added with fp32 atomic adds to `sums` [N,H] fp32 (caller's scratch, cleared by the call), and

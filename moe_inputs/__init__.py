@@ -61,6 +61,7 @@ class MoEConfig:
     score_mode: int
     zipf_s: float   # 0 -> uniform routing, else Zipf exponent of expert popularity
     seed: int
+    bias_gain: float = 0.0   # != 0 (with zipf_s == 0): router bias = bias_gain * a fixed seeded pattern (mild skew)
 
     @property
     def R(self) -> int:
@@ -205,6 +206,14 @@ def router_bias(cfg: MoEConfig) -> np.ndarray | None:
     """Per-expert logit bias that skews expert popularity: b_e = beta * ln(p_e / max p),
     beta = sqrt(6)/pi (the scale of a Gumbel whose variance matches the unit
     Gaussian logit noise).  None for uniform routing."""
+    if cfg.zipf_s == 0.0 and cfg.bias_gain != 0.0:
+        # a mild, graded skew: the experts' seeded ranks, centred and scaled to unit variance, times the
+        # gain (imbalance sweeps search the gain that gives a wanted spread of the experts' token shares)
+        order = np.argsort(raw_u64(cfg.seed, STREAM_RANK_PERM, 0, cfg.E), kind="stable")
+        z = np.empty(cfg.E, dtype=np.float64)
+        z[order] = np.arange(cfg.E, dtype=np.float64)
+        z = (z - z.mean()) / (z.std() if cfg.E > 1 else 1.0)
+        return (cfg.bias_gain * z).astype(np.float32)
     if cfg.zipf_s == 0.0:
         return None
     p = popularity(cfg)

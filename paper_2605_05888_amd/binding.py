@@ -12,7 +12,8 @@ BF16, F32 = 0, 1
 SCORE_SOFTMAX_TOPK, SCORE_SIGMOID_TOPK = 0, 1
 OP_ROUTE, OP_DISPATCH_LAYOUT, OP_GROUPED_FFN = 0, 1, 2
 
-_ERR_NAMES = {-1: "MOE_ERR_ARG", -2: "MOE_ERR_UNSUPPORTED", -3: "MOE_ERR_WORKSPACE", -4: "MOE_ERR_LAUNCH"}
+_ERR_NAMES = {-1: "MOE_ERR_ARG", -2: "MOE_ERR_UNSUPPORTED", -3: "MOE_ERR_WORKSPACE", -4: "MOE_ERR_LAUNCH",
+              -5: "MOE_ERR_STATE"}
 
 _c_i64, _c_int, _c_vp, _c_sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 
@@ -30,6 +31,7 @@ _SIGNATURES = {
     "moe_grouped_ffn": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp,
                                  _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
     "moe_ffn_schedule": (_c_int, [_c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_sz, _c_vp]),
+    "moe_ffn_status": (_c_int, [_c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_sz, _c_vp]),
     "moe_ffn_gate_up": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp,
                                  _c_vp, _c_sz, _c_vp]),
     "moe_ffn_gate_up_gather": (_c_int, [_c_vp, _c_int, _c_i64, _c_int, _c_i64, _c_i64, _c_int, _c_vp, _c_vp,
@@ -192,6 +194,12 @@ def moe_ffn_schedule(dtype: int, M: int, H: int, F: int, seg_offsets, ws):
     wp, wb = _ws_args(ws)
     _check(load_library().moe_ffn_schedule(dtype, M, H, F, seg_offsets.numel() - 1, _ptr(seg_offsets), wp, wb,
                                            _stream()))
+
+
+def moe_ffn_status(dtype: int, M: int, H: int, F: int, E_local: int, ws):
+    """Waits for the current stream; raises MoEHubError(MOE_ERR_STATE) if a GEMM step found no schedule."""
+    wp, wb = _ws_args(ws)
+    _check(load_library().moe_ffn_status(dtype, M, H, F, E_local, wp, wb, _stream()))
 
 
 def moe_ffn_gate_up(xp, seg_offsets, W_gate, W_up, ws):

@@ -27,6 +27,31 @@ FLAGS = [
 ]
 
 
+# The grouped GEMM's tall tiles (csrc/grouped_gemm.h, `xa`) keep an operand in vector registers that
+# hand-written buffer loads fill while hand-written matrix instructions are still to read them; the
+# compiler is not told, and the kernel is correct only as long as it never copies or reuses those
+# registers inside the K loop.  That was checked in the generated code of the compilers listed here
+# (and is checked on the GPU by the test that reverses every expert segment and expects the same bits).
+# Another compiler may schedule differently: read the listing again before adding it.
+TESTED_COMPILERS = ("7.2.26015",)
+
+
+def check_compiler() -> str:
+    out = subprocess.run([HIPCC, "--version"], capture_output=True, text=True).stdout
+    version = next((l.split(":", 1)[1].strip() for l in out.splitlines() if l.startswith("HIP version")), "unknown")
+    if not any(version.startswith(v) for v in TESTED_COMPILERS):
+        if os.environ.get("MOE_HUB_UNTESTED_COMPILER") != "1":
+            raise RuntimeError(
+                f"hipcc reports HIP version {version}; this library was checked with {TESTED_COMPILERS}. "
+                "The tall-tile code of csrc/grouped_gemm.h relies on the compiler leaving the registers of "
+                "`xa` alone inside the K loop: inspect the listing of grouped_gemm_bf16 (no instruction but "
+                "the hand-written buffer loads and v_mfma may touch them), run "
+                "tests/test_gpu_parity.py::test_ffn_remainder_rows_riding_with_the_last_full_tile, then add "
+                "the version to TESTED_COMPILERS or set MOE_HUB_UNTESTED_COMPILER=1.")
+        sys.stderr.write(f"warning: untested hipcc (HIP version {version})\n")
+    return version
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
@@ -41,6 +66,7 @@ def _compile(src: str) -> str:
 
 
 def build(verbose: bool = True) -> str:
+    check_compiler()
     os.makedirs(OBJ, exist_ok=True)
     with concurrent.futures.ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
         objs = list(ex.map(_compile, SOURCES))

@@ -20,7 +20,13 @@ int fail(int code, const char *fmt, ...)
     return code;
 }
 
-void clear_error() { g_err[0] = 0; }
+// Entry of every call: forget the last message, and a HIP error that the caller's own earlier work
+// left pending (it would otherwise be reported as a failed launch of ours).
+void clear_error()
+{
+    g_err[0] = 0;
+    (void)hipGetLastError();
+}
 
 int check_launch(const char *what)
 {
@@ -197,6 +203,8 @@ extern "C" int moe_permute(const void *x, int dtype, int64_t N, int64_t H, int K
     MOE_TRY(check_rows("H", H, dtype));
     if (N < 0 || K < 1 || N * (int64_t)K >= ((int64_t)1 << 31))
         return fail(MOE_ERR_ARG, "need N >= 0, K >= 1, N*K < 2^31 (got N=%lld, K=%d)", (long long)N, K);
+    if (K > kWave)
+        return fail(MOE_ERR_UNSUPPORTED, "moe_permute supports K <= %d (got %d)", kWave, K);
     if (N == 0)
         return MOE_OK;
     MOE_NEED(x);
@@ -243,6 +251,17 @@ extern "C" int moe_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int 
     if (M == 0)
         return MOE_OK;
     return launch_ffn_schedule(dtype, M, H, F, E_local, seg_offsets, ws, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int moe_ffn_status(int dtype, int64_t M, int64_t H, int64_t F, int E_local, const void *ws,
+                              size_t ws_bytes, void *stream)
+{
+    clear_error();
+    int32_t dummy_seg = 0; // check_ffn_common only tests seg_offsets for NULL
+    MOE_TRY(check_ffn_common(dtype, M, H, F, E_local, &dummy_seg, const_cast<void *>(ws), ws_bytes));
+    if (M == 0 || dtype == MOE_F32)
+        return MOE_OK;
+    return ffn_status(M, H, F, E_local, ws, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int moe_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,

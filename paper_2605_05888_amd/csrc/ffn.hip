@@ -16,6 +16,8 @@
 // together share weight tiles; workgroup ids are spread so that each XCD's L2
 // sees a compact patch of that order.  Nothing about the routing result is read
 // on the host.
+#include <atomic>
+
 #include "common.h"
 #include "grouped_gemm.h"
 
@@ -129,6 +131,7 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
         const int64_t wl = (int64_t)len[1] * kLightCost, wh = (int64_t)len[0] * kHeavyCost;
         hdr->light_slots = wl + wh > 0 ? (int32_t)((32 * wl + (wl + wh) / 2) / (wl + wh)) : 0;
         hdr->done = 0;
+        hdr->error = 0;
         hdr->magic = kTableMagic;
         hdr->rows = (int32_t)M;
         for (int s = 0; s < 2; ++s)
@@ -291,17 +294,35 @@ size_t ffn_workspace_bytes(int64_t M, int64_t H, int64_t F, int E_local, int dty
     return make_plan(M, H, F, E_local).total;
 }
 
+// Per-device facts, cached on first use.  Entries are written with relaxed atomics and every writer
+// stores the same value, so threads that race on the first call of a device do no harm.
+constexpr int kMaxDevices = 64;
+static int current_device()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return -1;
+    return dev;
+}
+
+static int compute_units()
+{
+    static std::atomic<int> cus[kMaxDevices];
+    const int dev = current_device();
+    int n = dev >= 0 ? cus[dev].load(std::memory_order_relaxed) : 0;
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev < 0 ? 0 : dev) != hipSuccess || n <= 0)
+            return kXcds * 32;
+        if (dev >= 0)
+            cus[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
 // workgroup slots of the device: compute units times the workgroups of this kernel a unit holds
 static int workgroup_slots(int per_cu)
 {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
-            return kXcds * 32;
-        cus = prop.multiProcessorCount;
-    }
+    const int cus = compute_units();
     int g = cus * per_cu / kXcds * kXcds; // whole rounds over the XCDs
     if (g > kMaxGemmWorkgroups)
         g = kMaxGemmWorkgroups / kXcds * kXcds;
@@ -319,11 +340,14 @@ static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const 
     size_t lds_bytes = Main::kLdsBytes;
     if constexpr (!std::is_void<Light>::value)
         lds_bytes = lds_bytes > Light::kLdsBytes ? lds_bytes : Light::kLdsBytes;
-    static bool attr_set = false; // raising the dynamic LDS limit is idempotent
-    if (!attr_set) {
+    // raising the dynamic LDS limit: once per device and kernel (idempotent, so a race only repeats it)
+    static std::atomic<uint64_t> raised{0};
+    const int dev = current_device();
+    if (dev < 0 || !(raised.load(std::memory_order_relaxed) >> dev & 1)) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        attr_set = true;
+        if (dev >= 0)
+            raised.fetch_or(uint64_t(1) << dev, std::memory_order_relaxed);
     }
     // persistent grid: the workgroups draw their tiles from the table's counters
     const int grid = workgroup_slots(Main::kLdsBytes <= 80 * 1024 ? 2 : 1);
@@ -418,6 +442,24 @@ int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     uint16_t *yb = static_cast<uint16_t *>(y);
     launch_gemm<BigTile<false>, ShallowTile<false>, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, kPatch, st);
     return check_launch("moe_ffn_down");
+}
+
+// Waits for `st`, then reads the two tables' error words.
+int ffn_status(int64_t M, int64_t H, int64_t F, int E_local, const void *ws, hipStream_t st)
+{
+    const FfnPlan p = make_plan(M, H, F, E_local);
+    const FfnWorkspace k = carve(p, const_cast<void *>(ws));
+    int32_t err[2] = {0, 0};
+    if (hipMemcpyAsync(&err[0], &k.hdr1->error, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipMemcpyAsync(&err[1], &k.hdr2->error, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+        return check_launch("moe_ffn_status") != MOE_OK ? MOE_ERR_LAUNCH
+                                                        : fail(MOE_ERR_LAUNCH, "moe_ffn_status: copy failed");
+    for (int g = 0; g < 2; ++g)
+        if (err[g] == kNoScheduleError)
+            return fail(MOE_ERR_STATE, "GEMM%d ran over a workspace that moe_ffn_schedule had not filled for M=%lld",
+                        g + 1, (long long)M);
+    return MOE_OK;
 }
 
 // ------------------------------------------------------------------------

@@ -67,13 +67,15 @@ struct TileTableHeader {
     int32_t done;           // workgroups that have left the kernel (the last one resets the counters)
     int32_t magic;          // kTableMagic once build_tile_table has filled the table ...
     int32_t rows;           // ... for this many rows
-    int32_t pad[2];
+    int32_t error;          // kNoScheduleError once a GEMM step found no table for its rows (cleared by the schedule)
+    int32_t pad;
     int32_t next[2][kXcds]; // per stream and XCD: tickets handed out so far
     int32_t pad2[8];
     int32_t ticket[kMaxGemmWorkgroups][8]; // per workgroup: tiles drawn by its first thread for all of it
 };
 constexpr size_t kTileTableHeaderBytes = 32768;
 constexpr int32_t kTableMagic = 0x4D6F4554;
+constexpr int32_t kNoScheduleError = 0x4E6F5363;
 static_assert(sizeof(TileTableHeader) <= kTileTableHeaderBytes, "header region");
 
 // Ticket j of an XCD -> position in a stream: each XCD takes runs of `patch` consecutive tiles, so
@@ -257,8 +259,13 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
     //      (LDS is full and a register cannot cross wavefronts): {tile, sequence number}, stored
     //      and loaded as one 8-byte unit.  A reader that finds an older sequence number reads
     //      again, so nobody waits for the store to land and nobody acts on a stale tile.
-    if (hdr->magic != kTableMagic || hdr->rows != (int32_t)M)
-        return; // no schedule for these rows in this workspace: nothing to go by
+    if (hdr->magic != kTableMagic || hdr->rows != (int32_t)M) {
+        // no schedule for these rows in this workspace: nothing to go by.  The host is not waiting for
+        // this kernel, so all it can do is leave a word that moe_ffn_status finds.
+        if (blockIdx.x == 0 && threadIdx.x == 0)
+            hdr->error = kNoScheduleError;
+        return;
+    }
     const int xcd = blockIdx.x % kXcds;
     int32_t *const my_ticket = hdr->ticket[blockIdx.x];
     const int len0 = hdr->len[0], len1 = hdr->len[1];

@@ -160,9 +160,6 @@ __global__ __launch_bounds__(kWave *kRtWaves) void router_logits_tiled(
     const int64_t n0 = ((int64_t)blockIdx.y * kRtWaves + wave) * kRtTok;
 
     // W_r tile rows are 64 bytes (16 experts); a load instruction fills 16 rows
-    const int64_t w_bytes = (int64_t)H * E * 4 - (int64_t)e0 * 4;
-    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float *>(W_r + e0), 0, (unsigned)(w_bytes > 0xFFFFFFFFll ? 0xFFFFFFFFll : w_bytes), 0x00020000);
     int w_off[kWLoads];
 #pragma unroll
     for (int g = 0; g < kWLoads; ++g) {
@@ -171,10 +168,6 @@ __global__ __launch_bounds__(kWave *kRtWaves) void router_logits_tiled(
     }
     // x: this wavefront's 8 token rows; a load instruction fills 1024 / kXRow token rows
     const int64_t n_left = N - n0; // may be <= 0 for the last workgroup: then nothing is in range
-    const int64_t x_bytes = n_left > 0 ? n_left * H * kXb : 0;
-    const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<unsigned char *>(static_cast<const unsigned char *>(x) + n0 * H * kXb), 0,
-        (unsigned)(x_bytes > 0xFFFFFFFFll ? 0xFFFFFFFFll : x_bytes), 0x00020000);
     constexpr int kLanesPerRow = kXRow / 16;
     int x_off[kXLoads];
 #pragma unroll
@@ -182,20 +175,32 @@ __global__ __launch_bounds__(kWave *kRtWaves) void router_logits_tiled(
         const int t = g * (kWave / kLanesPerRow) + lane / kLanesPerRow;
         x_off[g] = (t * H + (lane % kLanesPerRow) * (16 / kXb)) * kXb;
     }
-    // a column range [k0, k0 + 128) that crosses H would read the next token's row: mask those lanes
+    // The position of a K tile goes into the base address and the byte count of the buffer
+    // resources, never into the loads' scalar offset: the range check covers the per-lane offset
+    // only, and what has to come back as zeros (rows of W_r past H, tokens past N) is decided by
+    // that check.  A column range [k0, k0 + 128) that crosses H makes the x loads of every token
+    // but the last read the start of the next token's row: finite values that meet W_r rows of
+    // zeros.
+    auto clamp32 = [](int64_t b) { return (unsigned)(b < 0 ? 0 : (b > 0xFFFFFFFFll ? 0xFFFFFFFFll : b)); };
     auto issue = [&](int kt) {
         unsigned char *st = lds + (kt & 1) * kStage;
         const int k0 = kt * kRtK;
+        const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float *>(W_r + (int64_t)k0 * E + e0), 0, clamp32(((int64_t)(H - k0) * E - e0) * 4),
+            0x00020000);
+        const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<unsigned char *>(static_cast<const unsigned char *>(x) + (n0 * H + k0) * kXb), 0,
+            clamp32(n_left > 0 ? (n_left * H - k0) * kXb : 0), 0x00020000);
 #pragma unroll
         for (int g = 0; g < kWLoads; ++g)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 rs_w, (__attribute__((address_space(3))) void *)(st + (wave * kWLoads + g) * 1024), 16,
-                w_off[g], k0 * E * 4, 0, 0);
+                w_off[g], 0, 0, 0);
 #pragma unroll
         for (int g = 0; g < kXLoads; ++g)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
                 rs_x, (__attribute__((address_space(3))) void *)(st + kWTile + wave * kXTile + g * 1024), 16,
-                x_off[g], k0 * kXb, 0, 0);
+                x_off[g], 0, 0, 0);
     };
 
     float acc[kRtTok * kRtExp];
@@ -235,8 +240,8 @@ __global__ __launch_bounds__(kWave *kRtWaves) void router_logits_tiled(
                 else
                     xv[t] = *reinterpret_cast<const float *>(xs + t * kXRow + row * 4);
             }
-            // columns past H: W_r came back as zeros, but x may hold the next row's values; the
-            // products are +-0 either way
+            // columns past H: W_r came back as zeros (x may hold the next row's values): the
+            // products are +-0
 #pragma unroll
             for (int t = 0; t < kRtTok; ++t)
 #pragma unroll

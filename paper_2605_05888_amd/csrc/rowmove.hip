@@ -14,6 +14,15 @@ namespace moe {
 
 constexpr int kTokensPerBlock = 4; // one wavefront each
 
+// Value of lane k (k wave-uniform) whatever lanes are active: the chunk loops below run a different
+// number of times per lane, and a cross-lane read that honours the execution mask (__shfl) returns 0
+// for a lane that has already left the loop.
+__device__ __forceinline__ int32_t lane_value(int32_t v, int k) { return __builtin_amdgcn_readlane(v, k); }
+__device__ __forceinline__ float lane_value(float v, int k)
+{
+    return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int32_t)__float_as_uint(v), k));
+}
+
 __global__ __launch_bounds__(kWave *kTokensPerBlock) void permute_rows(
     const u32x4 *__restrict__ x, int chunks, int64_t N, int K,
     const int32_t *__restrict__ slot_of_row, u32x4 *__restrict__ xp)
@@ -32,7 +41,7 @@ __global__ __launch_bounds__(kWave *kTokensPerBlock) void permute_rows(
         u32x4 v2 = __builtin_nontemporal_load(src + c + 2 * kWave);
         u32x4 v3 = __builtin_nontemporal_load(src + c + 3 * kWave);
         for (int k = 0; k < K; ++k) {
-            u32x4 *dst = xp + (int64_t)__shfl(my_slot, k) * chunks + c;
+            u32x4 *dst = xp + (int64_t)lane_value(my_slot, k) * chunks + c;
             dst[0] = v0;
             dst[kWave] = v1;
             dst[2 * kWave] = v2;
@@ -42,7 +51,7 @@ __global__ __launch_bounds__(kWave *kTokensPerBlock) void permute_rows(
     for (; c < chunks; c += kWave) {
         u32x4 v = __builtin_nontemporal_load(src + c);
         for (int k = 0; k < K; ++k)
-            xp[(int64_t)__shfl(my_slot, k) * chunks + c] = v;
+            xp[(int64_t)lane_value(my_slot, k) * chunks + c] = v;
     }
 }
 
@@ -69,8 +78,8 @@ __global__ __launch_bounds__(kWave *kTokensPerBlock) void combine_rows(
             for (int i = 0; i < 8; ++i)
                 acc[u][i] = 0.0f;
         for (int k = 0; k < K; ++k) { // ascending k: the order of the sum is part of the contract
-            const float w = __shfl(my_w, k);
-            const u32x4 *src = y + (int64_t)__shfl(my_slot, k) * chunks + c;
+            const float w = lane_value(my_w, k);
+            const u32x4 *src = y + (int64_t)lane_value(my_slot, k) * chunks + c;
             u32x4 v[kU];
 #pragma unroll
             for (int u = 0; u < kU; ++u)
@@ -115,8 +124,6 @@ __global__ __launch_bounds__(kWave *kTokensPerBlock) void combine_rows(
 int launch_permute(const void *x, int64_t row_bytes, int64_t N, int K, const int32_t *slot_of_row,
                    void *xp, hipStream_t st)
 {
-    if (K > kWave)
-        return fail(MOE_ERR_UNSUPPORTED, "moe_permute supports K <= %d (got %d)", kWave, K);
     const int chunks = (int)(row_bytes / 16);
     const unsigned blocks = (unsigned)ceil_div(N, kTokensPerBlock);
     hipLaunchKernelGGL(permute_rows, dim3(blocks), dim3(kWave * kTokensPerBlock), 0, st,

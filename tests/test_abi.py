@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
                           "moe_dispatch_layout_arrival",
                           "moe_permute", "moe_grouped_ffn", "moe_combine",
                           "moe_ffn_schedule", "moe_ffn_gate_up", "moe_ffn_gate_up_gather", "moe_ffn_down",
-                          "moe_ffn_down_combine"}
+                          "moe_ffn_down_combine", "moe_ffn_status"}
     lib = ctypes.CDLL(hub.lib_path()) if os.path.exists(hub.lib_path()) else hub.load_library()
     for n in names:
         assert hasattr(lib, n), n
@@ -49,6 +49,8 @@ ALIGNED = 0x1000   # a fake, well-aligned, never-dereferenced pointer: every cas
     (lambda L: L.moe_permute(None, hub.BF16, 4, 64, 2, ALIGNED, ALIGNED, ALIGNED, None), -1, "NULL"),
     (lambda L: L.moe_permute(ALIGNED + 2, hub.BF16, 4, 64, 2, ALIGNED, ALIGNED, ALIGNED, None), -1, "aligned"),
     (lambda L: L.moe_permute(ALIGNED, hub.BF16, 1 << 30, 64, 4, ALIGNED, ALIGNED, ALIGNED, None), -1, "2^31"),
+    (lambda L: L.moe_permute(ALIGNED, hub.BF16, 4, 64, 65, ALIGNED, ALIGNED, ALIGNED, None), -2, "K <= 64"),
+    (lambda L: L.moe_ffn_status(hub.BF16, 100, 64, 64, 2, ALIGNED, 16, None), -3, "workspace"),
     (lambda L: L.moe_route(ALIGNED, hub.BF16, 4, 64, ALIGNED, None, 8, 9, 0, ALIGNED, ALIGNED, ALIGNED, None, 0, None),
      -1, "K"),
     (lambda L: L.moe_route(ALIGNED, hub.BF16, 4, 64, ALIGNED, None, 4096, 2, 0, ALIGNED, ALIGNED, ALIGNED, None, 0,

@@ -18,6 +18,16 @@ def test_traffic_figures_come_from_the_committed_counter_summary():
     sys.path.insert(0, ROOT)
     import bench
     for workload, kernel in (("mixtral", "ffn_gate_up"), ("mixtral", "ffn_down"), ("dsv3_ep", "ffn_gate_up")):
-        t = bench.measured_traffic(workload, kernel)
+        t, src = bench.profiled_traffic(workload, kernel)
         assert t is not None and 1e9 < t < 1e11, (workload, kernel, t)
-    assert bench.measured_traffic("tiny", "ffn_gate_up") is None             # never measured: reported as null
+        assert src.startswith("profiles/")
+    assert bench.profiled_traffic("tiny", "ffn_gate_up") == (None, None)     # never measured: reported as null
+
+
+def test_default_workload_is_the_largest_single_gpu_configuration_and_the_others_ride_along():
+    sys.path.insert(0, ROOT)
+    import bench
+    import moe_inputs as mi
+    flops = {n: c.N * c.K * c.H * c.F for n, c in mi.CONFIGS.items()}
+    assert bench.DEFAULT_WORKLOAD == max(flops, key=flops.get) == "dsv3"
+    assert set(bench.DEFAULT_ALSO.split(",")) >= {"mixtral", "gptoss", "dsv3_ep"}

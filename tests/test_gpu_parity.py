@@ -169,6 +169,64 @@ def test_permute_and_combine_parity(G, name):
         G.check_close(G.host(out), want, *tol, what="combine")
 
 
+@pytest.mark.parametrize("N,H,K,dtype", [(37, 520, 2, mi.BF16), (21, 576, 16, mi.BF16), (29, 260, 2, mi.F32),
+                                         (10, 8, 8, mi.BF16), (13, 2056, 3, mi.BF16), (6, 1032, 32, mi.BF16)])
+def test_row_moves_with_fewer_chunks_than_copies_in_the_last_round(G, N, H, K, dtype):
+    """Row lengths whose count of 16-byte chunks leaves fewer lanes in a wavefront's last round than the
+    token has copies (chunks % 64 in [1, K), or the same after the four-at-a-time rounds): the slot and
+    the weight of copy k must reach the lanes still at work although lane k itself is not among them."""
+    import moe_inputs.device as mid
+    import dataclasses
+    E = max(K, 4)
+    cfg = dataclasses.replace(mi.CONFIGS["tiny"], N=N, H=H, E=E, K=K, dtype=dtype, seed=77)
+    _say("row moves", cfg)
+    x = mi.host_tensor(cfg, mi.STREAM_X)
+    rng = np.random.default_rng(H + K)
+    idx = _random_idx(rng, N, E, K, 0)
+    lay = oracle.layout(idx, E, 1)
+    dlay = {k: mid.to_device(v) for k, v in lay.items()}
+    xp = G.gpu_permute(mid.to_device(x), K, dlay)
+    want_xp = oracle.permute(x, K, lay["slot_of_row"])
+    assert np.array_equal(G.host(xp), want_xp)
+    w = rng.random((N, K)) + 0.1
+    w /= w.sum(axis=1, keepdims=True)
+    w32 = w.astype(np.float32)
+    y = mi.host_tensor(dataclasses.replace(cfg, N=N * K, seed=78), mi.STREAM_X)
+    out = G.gpu_combine(mid.to_device(y), K, dlay["slot_of_row"], mid.to_device(w32))
+    want = oracle.combine(y, K, lay["slot_of_row"], w32.astype(np.float64))
+    tol = (2e-2, 4e-3) if dtype == mi.BF16 else (1e-5, 1e-6)
+    G.check_close(G.host(out), want, *tol, what="combine")
+
+
+@pytest.mark.parametrize("N,H,E,K,dtype", [(45, 192, 8, 2, mi.BF16), (70, 2880 // 8, 128, 4, mi.BF16),
+                                           (33, 200, 12, 3, mi.F32), (64, 72, 256, 8, mi.BF16)])
+def test_route_reads_nothing_outside_its_operands(G, N, H, E, K, dtype):
+    """x and W_r are views into the middle of larger buffers filled with NaN; H is not a multiple of the
+    router's K tile of 128, so its last tile hangs over the end of W_r and of the last token's row.
+    Whatever is fetched from beyond an operand would turn logits into NaN: they must equal the oracle's
+    bit for bit."""
+    import moe_inputs.device as mid
+    import dataclasses
+    import torch
+    cfg = dataclasses.replace(mi.CONFIGS["tiny"], N=N, H=H, E=E, K=K, dtype=dtype, seed=13)
+    _say("route inside poisoned memory", cfg)
+    x, Wr = mi.host_tensor(cfg, mi.STREAM_X), mi.host_tensor(cfg, mi.STREAM_W_ROUTER)
+    bias = (np.arange(E) % 5).astype(np.float32) / 8
+    o_idx, o_w, o_lg = oracle.route(x, Wr, bias, K, oracle.SOFTMAX_TOPK)
+    pad = 1 << 16                                                # elements of NaN on either side
+    dt = torch.bfloat16 if dtype == mi.BF16 else torch.float32
+    xbuf = torch.full((pad + N * H + pad,), float("nan"), dtype=dt, device="cuda:0")
+    wbuf = torch.full((pad + H * E + pad,), float("nan"), dtype=torch.float32, device="cuda:0")
+    dx = mid.to_device(x)
+    xbuf[pad:pad + N * H] = (dx.view(dt) if dx.dtype != dt else dx).reshape(-1)
+    wbuf[pad:pad + H * E] = mid.to_device(Wr).reshape(-1)
+    xv, wv = xbuf[pad:pad + N * H].view(N, H), wbuf[pad:pad + H * E].view(H, E)
+    idx, w, lg = G.gpu_route(xv, wv, mid.to_device(bias), K, oracle.SOFTMAX_TOPK)
+    assert np.array_equal(G.host(lg).view(np.uint32), o_lg.view(np.uint32))
+    assert np.array_equal(G.host(idx), o_idx)
+    assert np.max(np.abs(G.host(w).astype(np.float64) - o_w)) <= 2e-6
+
+
 def _segments(rng, M, E, empty=()):
     cuts = np.sort(rng.integers(0, M + 1, size=E - 1))
     seg = np.concatenate([[0], cuts, [M]]).astype(np.int32)
@@ -401,8 +459,9 @@ def test_down_projection_with_combine_in_its_epilogue(G, name):
         G.check_close(got, G.as_f64(ref), 2e-2, 4e-3, what="against moe_ffn_down + moe_combine")
 
 
-def test_ffn_gemm_without_schedule_does_nothing(G):
-    """A workspace no schedule was built in holds no tile table: the GEMM steps leave their outputs alone."""
+def test_ffn_gemm_without_schedule_writes_nothing_and_says_so(G):
+    """A workspace no schedule was built in holds no tile table: the GEMM steps leave their outputs alone
+    (the calls cannot fail: nobody waits for the device), and moe_ffn_status reports it afterwards."""
     import moe_inputs.device as mid
     import dataclasses
     import torch
@@ -413,16 +472,28 @@ def test_ffn_gemm_without_schedule_does_nothing(G):
     seg = mid.to_device(np.array([0, 100, 300], np.int32))
     ws = torch.zeros(hub.workspace_bytes(hub.OP_GROUPED_FFN, N=cfg.N, H=cfg.H, E=cfg.E, F=cfg.F), dtype=torch.uint8,
                      device="cuda:0")
+    a_bytes = cfg.N * cfg.F * 2
+    status = lambda M: hub.moe_ffn_status(hub.BF16, M, cfg.H, cfg.F, cfg.E, ws)
+    status(cfg.N)                                                        # nothing has run yet
     y = torch.full((cfg.N, cfg.H), 3.0, dtype=torch.bfloat16, device="cuda:0")
     hub.moe_ffn_gate_up(xp, seg, Wg, Wu, ws)
     hub.moe_ffn_down(seg, Wd, y, ws)
     torch.cuda.synchronize()
-    assert not ws.any() and bool((y == 3.0).all())
+    assert not ws[:a_bytes].any() and bool((y == 3.0).all())
+    with pytest.raises(hub.MoEHubError) as err:
+        status(cfg.N)
+    assert err.value.code == -5
     hub.moe_ffn_schedule(hub.BF16, cfg.N - 44, cfg.H, cfg.F, seg, ws)     # a schedule for another row count
+    status(cfg.N - 44)                                                   # the schedule clears the word
     hub.moe_ffn_gate_up(xp, seg, Wg, Wu, ws)
     hub.moe_ffn_down(seg, Wd, y, ws)
     torch.cuda.synchronize()
     assert bool((y == 3.0).all())
+    hub.moe_ffn_schedule(hub.BF16, cfg.N, cfg.H, cfg.F, seg, ws)          # the right one: all is well
+    hub.moe_ffn_gate_up(xp, seg, Wg, Wu, ws)
+    hub.moe_ffn_down(seg, Wd, y, ws)
+    status(cfg.N)
+    assert bool((y != 3.0).any())
 
 
 def test_grouped_ffn_leaves_rows_outside_segments_untouched(G):

@@ -64,6 +64,41 @@ def test_fused_multiply_add_is_fused():
     assert oracle.logit_r64(x, w) == np.float32(float(a) * float(b))  # rounded product
 
 
+@pytest.mark.parametrize("H,E,bf16", [(70, 3, False), (130, 5, True), (64, 2, False)])
+def test_logits_with_bias_match_exact_rational_bruteforce(H, E, bf16):
+    """The bias enters after the six folding rounds, as ONE fp32 addition to the folded sum: every
+    operation of the whole logit, the bias add included, rounded from its exact rational value.  Biases
+    are large against the last place of the sum, so a bias folded into a partial sum before the rounds
+    (or added in higher precision) gives other bits."""
+    rng = np.random.default_rng(100 + H)
+    N = 4
+    x = rng.standard_normal((N, H)).astype(np.float32)
+    if bf16:
+        xb = mi.f32_to_bf16_bits(x)
+        x_val, x_arg = mi.bf16_bits_to_f32(xb), xb
+    else:
+        x_val, x_arg = x, x
+    W = (rng.standard_normal((H, E)) / np.sqrt(H)).astype(np.float32)
+    b = (rng.standard_normal(E) * 3).astype(np.float32)
+    got = oracle.logits(x_arg, W, b)
+    differs_if_folded_early = 0
+    for n in range(N):
+        for e in range(E):
+            want = add_f32(_r64_exact(x_val[n], W[:, e]), b[e])
+            assert got[n, e].tobytes() == want.tobytes(), (n, e)
+            # the planted alternative: bias as the starting value of partial 0
+            p = [np.float32(0.0)] * 64
+            p[0] = b[e]
+            for h in range(H):
+                p[h % 64] = fma_f32(x_val[n, h], W[h, e], p[h % 64])
+            s = 32
+            while s >= 1:
+                p = [add_f32(p[l], p[l ^ s]) for l in range(64)]
+                s //= 2
+            differs_if_folded_early += int(p[0].tobytes() != want.tobytes())
+    assert differs_if_folded_early > 0          # the pin can tell the two apart on these inputs
+
+
 def test_logits_close_to_fp64_dot_and_not_transposed():
     rng = np.random.default_rng(0)
     N, H, E = 9, 320, 5                     # H != E: a transposed W_r cannot pass
