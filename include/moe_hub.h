@@ -62,6 +62,9 @@ enum { MOE_OP_ROUTE = 0, MOE_OP_DISPATCH_LAYOUT = 1, MOE_OP_GROUPED_FFN = 2 };
 
 enum { MOE_MAX_EXPERTS = 1024, MOE_MAX_TOPK = 32 };
 
+/* Size of the histogram array built into the library for moe_dispatch_layout_static. */
+#define MOE_LAYOUT_STATIC_MAX_BYTES (4u << 20)
+
 /* Text of the last error raised on the calling thread ("" if none). */
 const char *moe_last_error(void);
 
@@ -116,6 +119,26 @@ int moe_dispatch_layout(const int32_t *topk_idx, int64_t N, int K, int E, int G,
                         int32_t *dest_counts, int32_t *dest_offsets,
                         int32_t *slot_of_row, int32_t *row_of_slot,
                         void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * moe_dispatch_layout for callers that cannot allocate device memory or pass a
+ * workspace they allocated: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments (without ws), same kernels and
+ * bit for bit the same outputs; the per-unit histograms go into an array of
+ * MOE_LAYOUT_STATIC_MAX_BYTES (4 MiB) that is part of the library's device image.
+ * The call allocates nothing and frees nothing.  Limit: moe_workspace_bytes(
+ * MOE_OP_DISPATCH_LAYOUT, N, 0, E, K, G, 0, 0) <= MOE_LAYOUT_STATIC_MAX_BYTES, i.e.
+ * ceil(N*K / 512) * E <= 2^20 (N*K = 131072 rows with E = 1024 experts fit four
+ * times over); beyond it MOE_ERR_UNSUPPORTED.  Each GPU holds its own copy of the
+ * array from the library's first use there until the process ends, and every call
+ * on that GPU uses it: calls that overlap on one GPU (two streams, two threads)
+ * race; calls in stream order on one stream do not.  The first call on a device
+ * looks the array's address up (hipGetSymbolAddress) with that device current.
+ */
+int moe_dispatch_layout_static(const int32_t *topk_idx, int64_t N, int K, int E, int G,
+                               int32_t *expert_counts, int32_t *expert_offsets,
+                               int32_t *dest_counts, int32_t *dest_offsets,
+                               int32_t *slot_of_row, int32_t *row_of_slot, void *stream);
 
 /*
  * Address resolution in arrival order (the allocation unit of Section IV-A3: a row

@@ -25,6 +25,8 @@ _SIGNATURES = {
                            _c_vp, _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
     "moe_dispatch_layout": (_c_int, [_c_vp, _c_i64, _c_int, _c_int, _c_int, _c_vp, _c_vp, _c_vp, _c_vp,
                                      _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
+    "moe_dispatch_layout_static": (_c_int, [_c_vp, _c_i64, _c_int, _c_int, _c_int, _c_vp, _c_vp, _c_vp,
+                                            _c_vp, _c_vp, _c_vp, _c_vp]),
     "moe_dispatch_layout_arrival": (_c_int, [_c_vp, _c_i64, _c_int, _c_int, _c_int, _c_vp, _c_vp, _c_vp,
                                              _c_vp, _c_vp, _c_vp, _c_vp]),
     "moe_permute": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp, _c_vp]),
@@ -149,6 +151,22 @@ def moe_dispatch_layout(topk_idx, E: int, G: int, expert_counts, expert_offsets,
     _check(load_library().moe_dispatch_layout(_ptr(topk_idx), N, K, E, G, _ptr(expert_counts),
                                               _ptr(expert_offsets), _ptr(dest_counts), _ptr(dest_offsets),
                                               _ptr(slot_of_row), _ptr(row_of_slot), wp, wb, _stream()))
+
+
+def moe_dispatch_layout_static(topk_idx, E: int, G: int, expert_counts, expert_offsets, dest_counts,
+                               dest_offsets, slot_of_row, row_of_slot):
+    import torch
+    N, K = topk_idx.shape
+    for name, t, n in (("expert_counts", expert_counts, E), ("expert_offsets", expert_offsets, E + 1),
+                       ("dest_counts", dest_counts, G), ("dest_offsets", dest_offsets, G + 1),
+                       ("slot_of_row", slot_of_row, N * K), ("row_of_slot", row_of_slot, N * K)):
+        _need(t, torch.int32, name)
+        assert t.numel() == n, name
+    _need(topk_idx, torch.int32, "topk_idx")
+    _check(load_library().moe_dispatch_layout_static(_ptr(topk_idx), N, K, E, G, _ptr(expert_counts),
+                                                     _ptr(expert_offsets), _ptr(dest_counts),
+                                                     _ptr(dest_offsets), _ptr(slot_of_row),
+                                                     _ptr(row_of_slot), _stream()))
 
 
 def moe_dispatch_layout_arrival(topk_idx, E: int, G: int, expert_counts, expert_offsets, dest_counts,

@@ -175,6 +175,24 @@ extern "C" int moe_dispatch_layout(const int32_t *topk_idx, int64_t N, int K, in
                          static_cast<hipStream_t>(stream));
 }
 
+extern "C" int moe_dispatch_layout_static(const int32_t *topk_idx, int64_t N, int K, int E, int G,
+                                          int32_t *expert_counts, int32_t *expert_offsets,
+                                          int32_t *dest_counts, int32_t *dest_offsets,
+                                          int32_t *slot_of_row, int32_t *row_of_slot, void *stream)
+{
+    clear_error();
+    MOE_TRY(check_routing_sizes(N, K, E));
+    if (G < 1 || E % G != 0)
+        return fail(MOE_ERR_ARG, "G must divide E (got E=%d, G=%d)", E, G);
+    if (!expert_counts || !expert_offsets || !dest_counts || !dest_offsets)
+        return fail(MOE_ERR_ARG, "count and offset outputs must not be NULL");
+    int64_t R = N * (int64_t)K;
+    if (R > 0 && (!topk_idx || !slot_of_row || !row_of_slot))
+        return fail(MOE_ERR_ARG, "topk_idx, slot_of_row and row_of_slot must not be NULL");
+    return launch_layout_static(topk_idx, R, E, G, expert_counts, expert_offsets, dest_counts,
+                                dest_offsets, slot_of_row, row_of_slot, static_cast<hipStream_t>(stream));
+}
+
 extern "C" int moe_dispatch_layout_arrival(const int32_t *topk_idx, int64_t N, int K, int E, int G,
                                            int32_t *expert_counts, int32_t *expert_offsets,
                                            int32_t *dest_counts, int32_t *dest_offsets,

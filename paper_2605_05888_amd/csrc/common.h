@@ -57,6 +57,9 @@ size_t layout_workspace_bytes(int64_t R, int E);
 int launch_layout(const int32_t *topk_idx, int64_t R, int E, int G, int32_t *expert_counts,
                   int32_t *expert_offsets, int32_t *dest_counts, int32_t *dest_offsets,
                   int32_t *slot_of_row, int32_t *row_of_slot, void *ws, hipStream_t st);
+int launch_layout_static(const int32_t *topk_idx, int64_t R, int E, int G, int32_t *expert_counts,
+                         int32_t *expert_offsets, int32_t *dest_counts, int32_t *dest_offsets,
+                         int32_t *slot_of_row, int32_t *row_of_slot, hipStream_t st);
 int launch_layout_arrival(const int32_t *topk_idx, int64_t R, int E, int G, int32_t *expert_counts,
                           int32_t *expert_offsets, int32_t *dest_counts, int32_t *dest_offsets,
                           int32_t *slot_of_row, int32_t *row_of_slot, hipStream_t st);

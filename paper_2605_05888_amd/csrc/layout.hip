@@ -10,6 +10,8 @@
 //           its cursors at offset[e] + unit_base[e][u] and walks its unit 64 rows
 //           at a time; inside a 64-row step the rank among equal experts comes
 //           from wavefront ballots, so the order is ascending r everywhere.
+#include <atomic>
+
 #include "common.h"
 
 namespace moe {
@@ -199,6 +201,55 @@ int launch_layout(const int32_t *topk_idx, int64_t R, int E, int G, int32_t *exp
                        topk_idx, R, E, G, nbits, U, unit_hist, expert_counts, expert_offsets,
                        dest_counts, dest_offsets, slot_of_row, row_of_slot);
     return check_launch("moe_dispatch_layout");
+}
+
+// ---------------------------------------------------------------------------
+// The same address resolution for callers that cannot hand over a workspace they allocated: the
+// per-unit histograms live in a fixed array in the library's own device image.  Every GPU the
+// library runs on holds one copy of the array (at its own address) until the process ends; all
+// calls on a GPU share it, so calls that overlap there race.  Nothing in it has to start at zero:
+// pass 1 writes every entry that passes 2 and 3 read.
+// ---------------------------------------------------------------------------
+constexpr size_t kLayoutScratchBytes = MOE_LAYOUT_STATIC_MAX_BYTES;
+static __device__ __align__(256) unsigned char scratch[kLayoutScratchBytes];
+
+// Device address of this GPU's copy of `scratch` (in host code the array's name is only a handle for
+// the runtime, never an address a kernel may use).  Looked up once per device, with that device
+// current; racing first calls all store the same value.
+static int scratch_address(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void *> cached[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return fail(MOE_ERR_LAUNCH, "moe_dispatch_layout_static: no current device");
+    void *p = cached[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr)
+            return fail(MOE_ERR_LAUNCH, "moe_dispatch_layout_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        cached[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return MOE_OK;
+}
+
+int launch_layout_static(const int32_t *topk_idx, int64_t R, int E, int G, int32_t *expert_counts,
+                         int32_t *expert_offsets, int32_t *dest_counts, int32_t *dest_offsets,
+                         int32_t *slot_of_row, int32_t *row_of_slot, hipStream_t st)
+{
+    const size_t need = layout_workspace_bytes(R, E);
+    if (need > kLayoutScratchBytes)
+        return fail(MOE_ERR_UNSUPPORTED,
+                    "moe_dispatch_layout_static: N*K=%lld rows over E=%d experts need %zu bytes of histograms, "
+                    "the built-in array holds %zu; use moe_dispatch_layout with a workspace",
+                    (long long)R, E, need, kLayoutScratchBytes);
+    void *ws = nullptr;
+    const int rc = scratch_address(&ws);
+    if (rc != MOE_OK)
+        return rc;
+    return launch_layout(topk_idx, R, E, G, expert_counts, expert_offsets, dest_counts, dest_offsets,
+                         slot_of_row, row_of_slot, ws, st);
 }
 
 // ---------------------------------------------------------------------------
