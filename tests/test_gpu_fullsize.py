@@ -1,9 +1,12 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
 
 Routing, layout and permutation are compared in full (bit-exact).  The expert FFN is
-compared on sampled rows the oracle computes one by one: first and last row of every
-non-empty expert segment plus random rows, and every slot of a few sampled tokens so that
-the combined layer output of those tokens is checked end to end.  Inputs are generated in
+compared on 500+ sampled rows the oracle computes one by one, chosen deterministically:
+first and last row of every non-empty expert segment, one row in every 32-row block of a few
+tiles of every kind the workload has (full, tall, ragged, shallow), evenly spaced rows, and
+every slot of a few sampled tokens so that the layer output of those tokens is checked end to
+end.  The combine step is compared in full: every token, against the oracle's combine of the
+GPU's own y.  Inputs are generated in
 HBM by the harness fill kernel (identical, bit for bit, to the host generator) and copied
 back for the oracle; nothing the oracle consumes comes from the library under test.
 """
@@ -107,6 +110,61 @@ def _sample_rows(rng, seg, per_expert):
     return np.unique(np.array(rows, dtype=np.int64))
 
 
+# what the grouped GEMM makes of an expert with `rows` rows (csrc/ffn.hip): at most 64 rows: one shallow
+# tile; otherwise tiles of 256 rows, a remainder of up to 64 rows riding with the last full tile ("tall"),
+# a longer remainder forming a ragged tile of its own
+TILE_ROWS, TALL_EXTRA, SHALLOW_ROWS = 256, 64, 64
+
+
+def _tiles_of(lo, hi):
+    """(kind, first row, rows) for every tile of the expert segment [lo, hi)."""
+    n = hi - lo
+    if n == 0:
+        return []
+    if n <= SHALLOW_ROWS:
+        return [("shallow", lo, n)]
+    full, rest = divmod(n, TILE_ROWS)
+    tiles = [("full", lo + i * TILE_ROWS, TILE_ROWS) for i in range(full)]
+    if full > 0 and 0 < rest <= TALL_EXTRA:
+        tiles[-1] = ("tall", lo + (full - 1) * TILE_ROWS, TILE_ROWS + rest)
+    elif rest > 0:
+        tiles.append(("ragged", lo + full * TILE_ROWS, rest))
+    return tiles
+
+
+def _block_sweep(first, rows):
+    """One row in every 32-row block of a tile, at a position inside the block that moves from block to block."""
+    out = []
+    for blk in range((rows + 31) // 32):
+        out.append(first + min(blk * 32 + (blk * 7 + 3) % 32, rows - 1))
+    return out
+
+
+def _deterministic_sample(seg, want=560, tiles_per_kind=3):
+    """First and last row of every expert; one row in every 32-row block of `tiles_per_kind` tiles of every
+    kind the workload has (full, tall, ragged, shallow), taken from experts spread over the range; then
+    evenly spaced rows until there are `want` of them."""
+    lo_all, hi_all = int(seg[0]), int(seg[-1])
+    rows, by_kind = [], {}
+    for e in range(len(seg) - 1):
+        lo, hi = int(seg[e]), int(seg[e + 1])
+        if hi > lo:
+            rows += [lo, hi - 1]
+        for t in _tiles_of(lo, hi):
+            by_kind.setdefault(t[0], []).append(t)
+    kinds = {}
+    for kind, tiles in by_kind.items():
+        pick = [tiles[i * (len(tiles) - 1) // max(tiles_per_kind - 1, 1)] for i in range(min(tiles_per_kind, len(tiles)))]
+        kinds[kind] = len(tiles)
+        for _, first, n in pick:
+            rows += _block_sweep(first, n)
+    rows = np.unique(np.array(rows, dtype=np.int64))
+    if rows.size < want and hi_all > lo_all:
+        fill = np.linspace(lo_all, hi_all - 1, want - rows.size + 2).astype(np.int64)
+        rows = np.unique(np.concatenate([rows, fill]))
+    return rows, kinds
+
+
 def _oracle_rows_by_expert(G, xp_h, seg, W_dev, rows):
     """Oracle FFN of `rows`, expert by expert (weights copied back one expert at a time)."""
     out = np.zeros((rows.size, xp_h.shape[1]), dtype=np.float64)
@@ -118,7 +176,7 @@ def _oracle_rows_by_expert(G, xp_h, seg, W_dev, rows):
     return out
 
 
-def test_full_ffn_and_combine_on_samples(G, S):
+def test_full_ffn_on_samples_and_combine_in_full(G, S):
     import torch
     s = _oracle_routing(G, S)
     name = s["name"]
@@ -139,12 +197,13 @@ def test_full_ffn_and_combine_on_samples(G, S):
     out = G.gpu_combine(y, cfg.K, s["lay"]["slot_of_row"], s["w"])
     torch.cuda.synchronize()
     rng = np.random.default_rng(cfg.seed + 100)
-    per_expert = 4 if El <= 8 else 1
     tokens = rng.choice(cfg.N, size=8, replace=False)
     tok_slots = o_lay["slot_of_row"].reshape(cfg.N, cfg.K)[tokens].ravel().astype(np.int64)
     local = (tok_slots >= lo) & (tok_slots < hi)
-    rows = np.unique(np.concatenate([_sample_rows(rng, seg_h, per_expert), tok_slots[local]]))
-    _say(f"   {name}: oracle FFN on {rows.size} sampled rows of {hi - lo}")
+    sample, kinds = _deterministic_sample(seg_h)
+    rows = np.unique(np.concatenate([sample, tok_slots[local]]))
+    _say(f"   {name}: oracle FFN on {rows.size} sampled rows of {hi - lo}; tiles by kind {kinds}")
+    assert rows.size >= min(500, hi - lo)
     want = _oracle_rows_by_expert(G, xp_h, seg_h, s["W"], rows)
     y_h = G.host(y[torch.from_numpy(rows).to(y.device)])
     ma, rl = G.check_close(y_h, want, 2e-2, 1e-2, what="ffn rows")
@@ -159,6 +218,60 @@ def test_full_ffn_and_combine_on_samples(G, S):
     got = G.host(out[torch.from_numpy(tokens).to(out.device)])
     ma, rl = G.check_close(got, o_out, 2e-2, 1e-2, what="layer output")
     _say(f"   out max-abs {ma:.3e} rel-L2 {rl:.3e}")
+    # the combine step in full: every token of `out` against the oracle's combine of the GPU's own y
+    y_all = G.host(y)
+    del y
+    o_all = oracle.combine(y_all, cfg.K, o_lay["slot_of_row"], s["o_w"])
+    ma, rl = G.check_close(G.host(out), o_all, 2e-2, 4e-3, what="combine, all tokens")
+    _say(f"   combine over all {cfg.N} tokens: max-abs {ma:.3e} rel-L2 {rl:.3e}")
+
+
+@pytest.mark.parametrize("N", [128, 512])
+def test_mixtral_shape_at_small_token_counts(G, N):
+    """The small end of the token-count sweep, at the full Mixtral H and F: every expert has a few dozen
+    rows (N = 128: shallow tiles only) or one ragged tile (N = 512).  Routing, layout and permutation in
+    full; the FFN on sampled rows; the layer output of the tokens whose rows were all sampled."""
+    import dataclasses
+    import torch
+    import moe_inputs.device as mid
+    import paper_2605_05888_amd as hub
+    _state.clear()
+    torch.cuda.empty_cache()
+    cfg = dataclasses.replace(mi.CONFIGS["mixtral"], N=N)
+    _say("mixtral shape,", N, "tokens")
+    x = mid.device_tensor(cfg, mi.STREAM_X)
+    W_r = mid.device_tensor(cfg, mi.STREAM_W_ROUTER)
+    W = tuple(mid.device_tensor(cfg, st) for st in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    idx, w, _ = G.gpu_route(x, W_r, None, cfg.K, cfg.score_mode, want_logits=False)
+    lay = G.gpu_layout(idx, cfg.E, cfg.G)
+    xp = G.gpu_permute(x, cfg.K, lay)
+    y = G.gpu_ffn(xp, lay["expert_offsets"], *W)
+    out = G.gpu_combine(y, cfg.K, lay["slot_of_row"], w)
+    torch.cuda.synchronize()
+    x_h = G.host(x)
+    o_idx, o_w, _ = oracle.route(x_h, G.host(W_r), None, cfg.K, cfg.score_mode)
+    o_lay = oracle.layout(o_idx, cfg.E, cfg.G)
+    o_xp = oracle.permute(x_h, cfg.K, o_lay["slot_of_row"])
+    assert np.array_equal(G.host(idx), o_idx)
+    for k, v in o_lay.items():
+        assert np.array_equal(G.host(lay[k]), v), k
+    assert np.array_equal(G.host(xp), o_xp)
+    seg = o_lay["expert_offsets"]
+    tokens = np.arange(0, N, max(1, N // 24))[:24]
+    tok_slots = o_lay["slot_of_row"].reshape(N, cfg.K)[tokens].ravel().astype(np.int64)
+    sample, kinds = _deterministic_sample(seg, want=96, tiles_per_kind=2)
+    rows = np.unique(np.concatenate([sample, tok_slots]))
+    _say(f"   rows per expert {np.diff(seg).tolist()}; tiles by kind {kinds}; {rows.size} sampled rows")
+    want = _oracle_rows_by_expert(G, o_xp, seg, W, rows)
+    ma, rl = G.check_close(G.host(y)[rows], want, 2e-2, 1e-2, what="ffn rows")
+    _say(f"   ffn max-abs {ma:.3e} rel-L2 {rl:.3e}")
+    pos = {int(r): i for i, r in enumerate(rows)}
+    y_c = np.stack([want[pos[int(r)]] for r in tok_slots])
+    o_out = oracle.combine(y_c, cfg.K, np.arange(tok_slots.size, dtype=np.int32), o_w[tokens])
+    ma, rl = G.check_close(G.host(out)[tokens], o_out, 2e-2, 1e-2, what="layer output")
+    _say(f"   out max-abs {ma:.3e} rel-L2 {rl:.3e}")
+    o_all = oracle.combine(G.host(y), cfg.K, o_lay["slot_of_row"], o_w)
+    G.check_close(G.host(out), o_all, 2e-2, 4e-3, what="combine, all tokens")
 
 
 def test_full_gate_up_with_fused_gather_is_bit_identical(G, S):
