@@ -124,8 +124,10 @@ class Layer:
         import moe_inputs.device as mid
         self.bias = None if bias is None else mid.to_device(bias)
 
-    def step(self, i, events=None, fused_gather=False, fused_combine=False):
-        """One pass of the layer.  fused_gather (single-device layers only): no permute; the gate/up GEMM
+    def step(self, i, events=None, fused_gather=False, fused_combine=False, one_launch=False):
+        """One pass of the layer.  one_launch: both GEMMs of the expert computation in one kernel, the second
+        consuming the first's rows as they arrive (the `ffn_gate_up` event pair then brackets that kernel and
+        `ffn_down` is empty).  fused_gather (single-device layers only): no permute; the gate/up GEMM
         fetches its rows from x through row_of_slot.  fused_combine: no y and no combine step; the down
         GEMM adds its gate-weighted rows into the tokens' fp32 sums."""
         hub, cfg = self.hub, self.cfg
@@ -146,12 +148,17 @@ class Layer:
             ffn_in, seg = s["xp"], s["off"]
         hub.moe_ffn_schedule(self.code, self.R, cfg.H, cfg.F, seg, s["ffn_ws"])
         rec(4)
-        if fused_gather:
+        if one_launch:
+            hub.moe_ffn_gate_up_down(ffn_in, seg, self.W_gate, self.W_up, self.W_down, s["y"], s["ffn_ws"])
+        elif fused_gather:
             hub.moe_ffn_gate_up_gather(s["x"], cfg.K, seg, s["row"], self.W_gate, self.W_up, s["ffn_ws"])
         else:
             hub.moe_ffn_gate_up(ffn_in, seg, self.W_gate, self.W_up, s["ffn_ws"])
         rec(5)
-        if fused_combine:
+        if one_launch:
+            rec(6)
+            hub.moe_combine(s["y"], cfg.K, s["slot"], s["w"], s["out"])
+        elif fused_combine:
             if self.sums is None:
                 self.sums = self.torch.empty((cfg.N, cfg.H), dtype=self.torch.float32, device="cuda:0")
             hub.moe_ffn_down_combine(cfg.K, seg, self.W_down, s["row"], s["w"], self.sums, s["out"], s["ffn_ws"])
@@ -282,6 +289,9 @@ def short_run(name, cfg, steps, warmup, nbuf_arg):
     torch.cuda.synchronize()
     ms, us = time_layer(layer, steps, warmup)
     out = summarise(cfg, layer, ms, us)
+    if out["dtype"] == "bf16":
+        o_ms, o_us = time_layer(layer, steps, min(3, warmup), one_launch=True)
+        out["ffn_one_launch"] = {"ms_per_step": o_ms, "ffn_us": o_us["ffn_gate_up"]}
     out["config"] = {"workload": f"{name}: {WORKLOAD_TEXT.get(name, name)}", "N": cfg.N, "H": cfg.H, "E": cfg.E,
                      "K": cfg.K, "F": cfg.F, "G": cfg.G, "activation_buffer_sets": nbuf}
     del layer
@@ -398,6 +408,13 @@ def main():
     torch.cuda.synchronize()
     result["layout_order"] = {"stable_us": la[0].elapsed_time(la[1]) * 1e3 / reps,
                               "arrival_us": la[1].elapsed_time(la[2]) * 1e3 / reps}
+    # Both GEMMs in one launch, the down projection's tiles starting as their rows arrive (the dependency-driven
+    # form): same bits; reported beside the layer, not as `value`.
+    if cfg.dtype == mi.BF16:
+        o_ms, o_us = time_layer(layer, args.steps, min(3, args.warmup), one_launch=True)
+        result["ffn_one_launch"] = {"ms_per_step": o_ms, "tokens_per_s": N / (o_ms * 1e-3), "ffn_us": o_us["ffn_gate_up"],
+                                    "ffn_us_two_launches": us["ffn_gate_up"] + us["ffn_down"],
+                                    "mfma_frac_both": 6.0 * R * H * F / (o_us["ffn_gate_up"] * 1e-6) / 1e12 / PEAK_BF16_TFLOPS}
     if not layer.ep:
         # Variant without a dispatch row move (a single device that computes every expert needs no send
         # buffer): the gate/up GEMM gathers its rows from x.  Reported beside the layer, not as `value`.

@@ -48,7 +48,7 @@ enum {
     MOE_ERR_UNSUPPORTED = -2, /* valid but not built (dtype, E too large, ...)    */
     MOE_ERR_WORKSPACE = -3,   /* workspace missing or smaller than required       */
     MOE_ERR_LAUNCH = -4,      /* the HIP runtime refused a launch                 */
-    MOE_ERR_STATE = -5        /* moe_ffn_status: a GEMM step ran without a schedule */
+    MOE_ERR_STATE = -5        /* moe_ffn_status: a GEMM step ran without a schedule or gave up a wait */
 };
 
 enum { MOE_BF16 = 0, MOE_F32 = 1 };
@@ -215,11 +215,43 @@ int moe_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
                     const void *W_gate, const void *W_up,
                     void *ws, size_t ws_bytes, void *stream);
 /*
+ * Both GEMMs of the expert computation in ONE launch, the second consuming the first's
+ * output as it becomes available: the software counterpart of the paper's data
+ * availability manager (Section IV-C: what each group of thread blocks depends on is
+ * known in advance, arrivals are counted, and a block is released as soon as its own
+ * data are complete instead of after a global barrier).  A workgroup works through the
+ * tiles of the gate/up projection and then goes on to tiles of the down projection; a
+ * down-projection tile needs the rows [m0, m0 + rows) of the activation a, complete over
+ * all F columns, and nothing else: every wavefront of a gate/up tile bumps that row
+ * tile's arrival counter (in the workspace) once its stores are acknowledged, and the
+ * down-projection tile starts when the counter is full.  The tail of the first GEMM and
+ * the head of the second overlap, and one launch replaces two.
+ *   moe_ffn_schedule -> moe_ffn_gate_up_down   (in stream order)
+ * gives bit for bit the y of moe_ffn_schedule -> moe_ffn_gate_up -> moe_ffn_down.  It may
+ * be launched again over the same schedule.  (moe_grouped_ffn runs the two separate
+ * launches, which are the faster form on this chip: the XCDs' L2 caches do not see each
+ * other's lines, so the gate/up projection has to store its result through to memory.)
+ * Arguments as in moe_grouped_ffn.  wait_limit: how many polls (about a microsecond
+ * each) a down-projection tile spends on its rows before its workgroup gives up; 0 = the
+ * default (seconds).  Every gate/up tile is drawn by a workgroup that waits for nothing
+ * before any down-projection tile is drawn, so a wait always ends; the limit turns a
+ * broken schedule into an exit instead of a hang: the workgroup leaves, sets the
+ * workspace's error word (moe_ffn_status then returns MOE_ERR_STATE) and y stays
+ * incomplete.  The call itself still returns MOE_OK.  MOE_F32: runs the two simple
+ * kernels one after the other.
+ */
+int moe_ffn_gate_up_down(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
+                         int E_local, const int32_t *seg_offsets,
+                         const void *W_gate, const void *W_up, const void *W_down,
+                         void *y, void *ws, size_t ws_bytes, int64_t wait_limit, void *stream);
+
+/*
  * Did every GEMM step launched over this workspace since the last moe_ffn_schedule
  * find its schedule?  The one call of the library that waits: it synchronises
  * `stream`, copies the workspace's two error words to the host and returns MOE_OK
  * or MOE_ERR_STATE (a bf16 GEMM step ran over a workspace that moe_ffn_schedule had
- * not filled for the same M, and wrote nothing).  For tests and debugging; the
+ * not filled for the same M, and wrote nothing; or a tile of moe_ffn_gate_up_down ran
+ * into its wait_limit).  For tests and debugging; the
  * hot path does not need it.  fp32 workspaces have no schedule: always MOE_OK.
  */
 int moe_ffn_status(int dtype, int64_t M, int64_t H, int64_t F, int E_local,

@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     workspace_bytes, moe_route, moe_dispatch_layout, moe_dispatch_layout_arrival, moe_dispatch_layout_static,
     moe_permute, moe_grouped_ffn, moe_combine,
     moe_ffn_schedule, moe_ffn_gate_up, moe_ffn_gate_up_gather, moe_ffn_down,
-    moe_ffn_down_combine, moe_ffn_status,
+    moe_ffn_down_combine, moe_ffn_status, moe_ffn_gate_up_down,
 )

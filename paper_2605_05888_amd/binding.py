@@ -33,6 +33,8 @@ _SIGNATURES = {
     "moe_grouped_ffn": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp,
                                  _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
     "moe_ffn_schedule": (_c_int, [_c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_sz, _c_vp]),
+    "moe_ffn_gate_up_down": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp,
+                                      _c_vp, _c_vp, _c_vp, _c_sz, _c_i64, _c_vp]),
     "moe_ffn_status": (_c_int, [_c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_sz, _c_vp]),
     "moe_ffn_gate_up": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp,
                                  _c_vp, _c_sz, _c_vp]),
@@ -212,6 +214,22 @@ def moe_ffn_schedule(dtype: int, M: int, H: int, F: int, seg_offsets, ws):
     wp, wb = _ws_args(ws)
     _check(load_library().moe_ffn_schedule(dtype, M, H, F, seg_offsets.numel() - 1, _ptr(seg_offsets), wp, wb,
                                            _stream()))
+
+
+def moe_ffn_gate_up_down(xp, seg_offsets, W_gate, W_up, W_down, y, ws, wait_limit: int = 0):
+    import torch
+    M, H = xp.shape
+    E_local, F, H2 = W_gate.shape
+    assert H2 == H and tuple(W_up.shape) == (E_local, F, H) and tuple(W_down.shape) == (E_local, H, F)
+    assert W_gate.dtype == W_up.dtype == W_down.dtype == xp.dtype == y.dtype
+    for t in (xp, W_gate, W_up, W_down, y):
+        assert t.is_cuda and t.is_contiguous()
+    _need(seg_offsets, torch.int32, "seg_offsets")
+    assert seg_offsets.numel() == E_local + 1 and y.numel() == M * H
+    wp, wb = _ws_args(ws)
+    _check(load_library().moe_ffn_gate_up_down(_ptr(xp), _dtype_code(xp), M, H, F, E_local, _ptr(seg_offsets),
+                                               _ptr(W_gate), _ptr(W_up), _ptr(W_down), _ptr(y), wp, wb,
+                                               wait_limit, _stream()))
 
 
 def moe_ffn_status(dtype: int, M: int, H: int, F: int, E_local: int, ws):

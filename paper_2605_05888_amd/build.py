@@ -52,9 +52,9 @@ def check_compiler() -> str:
     return version
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(src: str, defines=(), obj_dir: str = OBJ) -> str:
+    obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
+    cmd = [HIPCC, *FLAGS, *[f"-D{d}" for d in defines], "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")
@@ -65,16 +65,19 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(verbose: bool = True) -> str:
+def build(verbose: bool = True, defines=(), out: str = LIB) -> str:
+    """Builds the library.  `defines` (NAME=VALUE strings) and `out` give a variant build next to the
+    default one, for timing two builds against each other (load it with MOE_HUB_LIBRARY=<out>)."""
     check_compiler()
-    os.makedirs(OBJ, exist_ok=True)
+    obj_dir = OBJ if out == LIB else OBJ + "_" + os.path.splitext(os.path.basename(out))[0]
+    os.makedirs(obj_dir, exist_ok=True)
     with concurrent.futures.ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+        objs = list(ex.map(lambda src: _compile(src, defines, obj_dir), SOURCES))
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs]
     subprocess.run(cmd, check=True)
     if verbose:
-        print(f"built {LIB}")
-    return LIB
+        print(f"built {out}")
+    return out
 
 
 def needs_build() -> bool:
@@ -87,4 +90,9 @@ def needs_build() -> bool:
 
 
 if __name__ == "__main__":
-    build()
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("-D", dest="defines", action="append", default=[], help="NAME=VALUE for the preprocessor")
+    ap.add_argument("--out", default=LIB)
+    a = ap.parse_args()
+    build(defines=a.defines, out=os.path.abspath(a.out))

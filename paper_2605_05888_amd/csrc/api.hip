@@ -382,6 +382,30 @@ extern "C" int moe_grouped_ffn(const void *xp, int dtype, int64_t M, int64_t H, 
     return launch_ffn_down(dtype, M, H, F, E_local, seg_offsets, W_down, y, ws, st);
 }
 
+extern "C" int moe_ffn_gate_up_down(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
+                                    int E_local, const int32_t *seg_offsets, const void *W_gate,
+                                    const void *W_up, const void *W_down, void *y, void *ws,
+                                    size_t ws_bytes, int64_t wait_limit, void *stream)
+{
+    clear_error();
+    MOE_TRY(check_ffn_common(dtype, M, H, F, E_local, seg_offsets, ws, ws_bytes));
+    if (wait_limit < 0)
+        return fail(MOE_ERR_ARG, "wait_limit must be >= 0 (got %lld)", (long long)wait_limit);
+    if (M == 0)
+        return MOE_OK;
+    MOE_NEED(xp);
+    MOE_NEED(W_gate);
+    MOE_NEED(W_up);
+    MOE_NEED(W_down);
+    MOE_NEED(y);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == MOE_BF16)
+        return launch_ffn_gate_up_down(xp, M, H, F, E_local, W_gate, W_up, W_down, y, ws, wait_limit, st);
+    // fp32 (correctness path): the two simple kernels, one after the other
+    MOE_TRY(launch_ffn_gate_up(xp, dtype, M, H, F, E_local, seg_offsets, W_gate, W_up, ws, st));
+    return launch_ffn_down(dtype, M, H, F, E_local, seg_offsets, W_down, y, ws, st);
+}
+
 extern "C" int moe_combine(const void *y, int dtype, int64_t N, int64_t H, int K,
                            const int32_t *slot_of_row, const float *topk_w, void *out,
                            void *stream)

@@ -80,6 +80,9 @@ int launch_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t 
 int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
                     const int32_t *seg_offsets, const void *W_down, void *y, void *ws,
                     hipStream_t st);
+int launch_ffn_gate_up_down(const void *xp, int64_t M, int64_t H, int64_t F, int E_local, const void *W_gate,
+                            const void *W_up, const void *W_down, void *y, void *ws, int64_t wait_limit,
+                            hipStream_t st);
 int ffn_status(int64_t M, int64_t H, int64_t F, int E_local, const void *ws, hipStream_t st);
 int launch_ffn_down_combine(int64_t N, int K, int64_t H, int64_t F, int E_local, const void *W_down,
                             const int32_t *row_of_slot, const float *topk_w, float *sums, void *out,

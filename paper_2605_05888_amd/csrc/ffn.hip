@@ -64,9 +64,12 @@ struct TableArgs {
 
 __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
     const int32_t *__restrict__ seg_offsets, int E_local, int64_t M, int BM, int extra, int light_rows,
-    TableArgs gemm1, TableArgs gemm2)
+    TableArgs gemm1, TableArgs gemm2, int32_t *__restrict__ ready)
 {
     const TableArgs &args = blockIdx.y == 0 ? gemm1 : gemm2;
+    if (blockIdx.y == 0) // arrival counters of the row tiles start at zero with every schedule
+        for (int64_t i = (int64_t)blockIdx.x * kSchedThreads + threadIdx.x; i < M; i += (int64_t)gridDim.x * kSchedThreads)
+            ready[i] = 0;
     const int n_tiles = args.n_tiles, max_tiles = args.max_tiles;
     TileTableHeader *__restrict__ hdr = args.hdr;
     TileEntry *__restrict__ table = args.table;
@@ -132,6 +135,8 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
         hdr->light_slots = wl + wh > 0 ? (int32_t)((32 * wl + (wl + wh) / 2) / (wl + wh)) : 0;
         hdr->done = 0;
         hdr->error = 0;
+        hdr->epoch = 0;
+        hdr->all_done = 0;
         hdr->magic = kTableMagic;
         hdr->rows = (int32_t)M;
         for (int s = 0; s < 2; ++s)
@@ -252,13 +257,20 @@ __global__ __launch_bounds__(256) void ffn_f32_down(const float *__restrict__ a,
 // of a wavefront go out under the first two k-steps after the barrier, the 8 A loads under the
 // other two.  An expert's last full tile also takes a remainder of up to 64 rows ("tall" tile).  Shallow: 64x256x64 tile for experts with few rows, four (A, B) unit pairs, so that
 // three K tiles of weights are in flight while one is multiplied. 
-template <bool kSwiglu> using BigTile = GemmCfg<256, 256, 2, 2, kSwiglu, 64, 5, 0x0044, 0x4400, 0, 64>;
+// MOE_WEIGHTS_AHEAD: the operand that uses the ring's spare unit to run one K tile further ahead is the
+// weights (1) or the activations (0).
+#ifndef MOE_WEIGHTS_AHEAD
+#define MOE_WEIGHTS_AHEAD 1
+#endif
+template <bool kSwiglu>
+using BigTile = GemmCfg<256, 256, 2, 2, kSwiglu, 64, 5, (MOE_WEIGHTS_AHEAD ? 0x4400 : 0x0044),
+                        (MOE_WEIGHTS_AHEAD ? 0x0044 : 0x4400), 0, 64, (MOE_WEIGHTS_AHEAD != 0)>;
 template <bool kSwiglu> using ShallowTile = GemmCfg<64, 256, 1, 4, kSwiglu, 64, 8, 0x1010, 0x2222, 1>;
 
 struct FfnPlan {
     int BM, out_cols1, out_cols2;
     int n_tiles1, n_tiles2, max_m_tiles;
-    size_t off_a, off_hdr1, off_tab1, off_hdr2, off_tab2, total;
+    size_t off_a, off_hdr1, off_tab1, off_hdr2, off_tab2, off_ready, total;
 };
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -283,6 +295,8 @@ static FfnPlan make_plan(int64_t M, int64_t H, int64_t F, int E_local)
     o += kTileTableHeaderBytes;
     p.off_tab2 = o;
     o = align_up(o + (size_t)p.max_m_tiles * p.n_tiles2 * sizeof(TileEntry), 256);
+    p.off_ready = o; // per row: arrival counter of the row tile that starts there (dependency-driven launches)
+    o = align_up(o + (size_t)M * sizeof(int32_t), 256);
     p.total = o;
     return p;
 }
@@ -329,6 +343,37 @@ static int workgroup_slots(int per_cu)
     return g < kXcds ? kXcds : g;
 }
 
+// Raises the kernel's dynamic LDS limit once per device (idempotent, so a race only repeats it).
+template <class Kernel>
+static void allow_lds(Kernel kern, size_t lds_bytes, std::atomic<uint64_t> &raised)
+{
+    const int dev = current_device();
+    if (dev < 0 || !(raised.load(std::memory_order_relaxed) >> dev & 1)) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)lds_bytes);
+        if (dev >= 0)
+            raised.fetch_or(uint64_t(1) << dev, std::memory_order_relaxed);
+    }
+}
+
+template <class Main, class Light>
+static size_t lds_bytes_of()
+{
+    size_t b = Main::kLdsBytes;
+    if constexpr (!std::is_void<Light>::value)
+        b = b > Light::kLdsBytes ? b : Light::kLdsBytes;
+    return b;
+}
+
+static GemmArgs gemm_args(const uint16_t *A, int64_t M, int Kdim, int Ndim, const uint16_t *B0, const uint16_t *B1,
+                          uint16_t *C, TileTableHeader *hdr, const TileEntry *table, int patch)
+{
+    GemmArgs g = {};
+    g.A = A, g.M = M, g.Kdim = Kdim, g.Ndim = Ndim, g.B0 = B0, g.B1 = B1, g.C = C, g.hdr = hdr, g.table = table;
+    g.patch = patch, g.gather_div = 1;
+    return g;
+}
+
 template <class Main, class Light, bool kSwiglu, bool kGather = false, bool kScatter = false>
 static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const uint16_t *B0,
                         const uint16_t *B1, uint16_t *C, TileTableHeader *hdr,
@@ -337,22 +382,14 @@ static void launch_gemm(const uint16_t *A, int64_t M, int Kdim, int Ndim, const 
                         const float *scatter_w = nullptr)
 {
     auto kern = grouped_gemm_bf16<Main, Light, kSwiglu, kGather, kScatter>;
-    size_t lds_bytes = Main::kLdsBytes;
-    if constexpr (!std::is_void<Light>::value)
-        lds_bytes = lds_bytes > Light::kLdsBytes ? lds_bytes : Light::kLdsBytes;
-    // raising the dynamic LDS limit: once per device and kernel (idempotent, so a race only repeats it)
+    const size_t lds_bytes = lds_bytes_of<Main, Light>();
     static std::atomic<uint64_t> raised{0};
-    const int dev = current_device();
-    if (dev < 0 || !(raised.load(std::memory_order_relaxed) >> dev & 1)) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (dev >= 0)
-            raised.fetch_or(uint64_t(1) << dev, std::memory_order_relaxed);
-    }
+    allow_lds(kern, lds_bytes, raised);
+    GemmArgs g = gemm_args(A, M, Kdim, Ndim, B0, B1, C, hdr, table, patch);
+    g.gather_rows = gather_rows, g.gather_div = gather_div, g.gather_bytes = gather_bytes, g.scatter_w = scatter_w;
     // persistent grid: the workgroups draw their tiles from the table's counters
     const int grid = workgroup_slots(Main::kLdsBytes <= 80 * 1024 ? 2 : 1);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(Main::kThreads), lds_bytes, st, A, M, Kdim, Ndim, B0, B1, C,
-                       hdr, table, patch, gather_rows, gather_div, gather_bytes, scatter_w);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(Main::kThreads), lds_bytes, st, g);
 }
 
 int check_ffn_shape(int dtype, int64_t H, int64_t F)
@@ -366,12 +403,15 @@ int check_ffn_shape(int dtype, int64_t H, int64_t F)
 
 // consecutive tiles each XCD takes at a time (see stream_position)
 constexpr int kPatch = 16;
+// polls (about a microsecond each) a dependent tile spends on its rows before it gives up: seconds
+constexpr int64_t kDefaultWaitLimit = (int64_t)1 << 22;
 
 struct FfnWorkspace {
     uint16_t *a;
     TileTableHeader *hdr1, *hdr2;
     TileEntry *tab1, *tab2;
     int max1, max2;
+    int32_t *ready;
 };
 
 static FfnWorkspace carve(const FfnPlan &p, void *ws)
@@ -385,6 +425,7 @@ static FfnWorkspace carve(const FfnPlan &p, void *ws)
     k.tab2 = reinterpret_cast<TileEntry *>(w + p.off_tab2);
     k.max1 = p.max_m_tiles * p.n_tiles1;
     k.max2 = p.max_m_tiles * p.n_tiles2;
+    k.ready = reinterpret_cast<int32_t *>(w + p.off_ready);
     return k;
 }
 
@@ -399,7 +440,8 @@ int launch_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     const int max_both = k.max1 > k.max2 ? k.max1 : k.max2;
     hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(max_both, kSchedThreads), 2),
                        dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, BigTile<true>::kExtra, kLightRows,
-                       TableArgs{p.n_tiles1, k.max1, k.hdr1, k.tab1}, TableArgs{p.n_tiles2, k.max2, k.hdr2, k.tab2});
+                       TableArgs{p.n_tiles1, k.max1, k.hdr1, k.tab1}, TableArgs{p.n_tiles2, k.max2, k.hdr2, k.tab2},
+                       k.ready);
     return check_launch("moe_ffn_schedule");
 }
 
@@ -444,6 +486,34 @@ int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     return check_launch("moe_ffn_down");
 }
 
+// Both GEMMs in one launch, the second consuming the first's rows tile by tile (after launch_ffn_schedule).
+int launch_ffn_gate_up_down(const void *xp, int64_t M, int64_t H, int64_t F, int E_local, const void *W_gate,
+                            const void *W_up, const void *W_down, void *y, void *ws, int64_t wait_limit,
+                            hipStream_t st)
+{
+    const FfnPlan p = make_plan(M, H, F, E_local);
+    const FfnWorkspace k = carve(p, ws);
+    using Main1 = BigTile<true>;
+    using Light1 = ShallowTile<true>;
+    using Main2 = BigTile<false>;
+    using Light2 = ShallowTile<false>;
+    auto kern = grouped_ffn_bf16<Main1, Light1, Main2, Light2>;
+    size_t lds_bytes = lds_bytes_of<Main1, Light1>();
+    lds_bytes = lds_bytes > lds_bytes_of<Main2, Light2>() ? lds_bytes : lds_bytes_of<Main2, Light2>();
+    static std::atomic<uint64_t> raised{0};
+    allow_lds(kern, lds_bytes, raised);
+    GemmArgs g1 = gemm_args(static_cast<const uint16_t *>(xp), M, (int)H, (int)F, static_cast<const uint16_t *>(W_gate),
+                            static_cast<const uint16_t *>(W_up), k.a, k.hdr1, k.tab1, kPatch);
+    GemmArgs g2 = gemm_args(k.a, M, (int)F, (int)H, static_cast<const uint16_t *>(W_down), nullptr,
+                            static_cast<uint16_t *>(y), k.hdr2, k.tab2, kPatch);
+    g1.ready = g2.ready = k.ready;
+    g1.hdr_dep = g2.hdr_dep = k.hdr1;
+    g1.ready_per_launch = g2.ready_per_launch = Main1::kWaves * p.n_tiles1;
+    g1.wait_limit = g2.wait_limit = wait_limit > 0 ? wait_limit : kDefaultWaitLimit;
+    hipLaunchKernelGGL(kern, dim3(workgroup_slots(1)), dim3(Main1::kThreads), lds_bytes, st, g1, g2);
+    return check_launch("moe_ffn_gate_up_down");
+}
+
 // Waits for `st`, then reads the two tables' error words.
 int ffn_status(int64_t M, int64_t H, int64_t F, int E_local, const void *ws, hipStream_t st)
 {
@@ -455,10 +525,14 @@ int ffn_status(int64_t M, int64_t H, int64_t F, int E_local, const void *ws, hip
         hipStreamSynchronize(st) != hipSuccess)
         return check_launch("moe_ffn_status") != MOE_OK ? MOE_ERR_LAUNCH
                                                         : fail(MOE_ERR_LAUNCH, "moe_ffn_status: copy failed");
-    for (int g = 0; g < 2; ++g)
+    for (int g = 0; g < 2; ++g) {
         if (err[g] == kNoScheduleError)
             return fail(MOE_ERR_STATE, "GEMM%d ran over a workspace that moe_ffn_schedule had not filled for M=%lld",
                         g + 1, (long long)M);
+        if (err[g] == kDependencyTimeout)
+            return fail(MOE_ERR_STATE, "GEMM%d gave up waiting for rows of the first GEMM (poll limit reached); "
+                                       "its output is incomplete", g + 1);
+    }
     return MOE_OK;
 }
 

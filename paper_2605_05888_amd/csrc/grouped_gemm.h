@@ -67,16 +67,28 @@ struct TileTableHeader {
     int32_t done;           // workgroups that have left the kernel (the last one resets the counters)
     int32_t magic;          // kTableMagic once build_tile_table has filled the table ...
     int32_t rows;           // ... for this many rows
-    int32_t error;          // kNoScheduleError once a GEMM step found no table for its rows (cleared by the schedule)
+    int32_t error;          // kNoScheduleError / kDependencyTimeout, see below (cleared by the schedule)
     int32_t pad;
     int32_t next[2][kXcds]; // per stream and XCD: tickets handed out so far
-    int32_t pad2[8];
+    // dependency-driven launches (both GEMMs in one kernel), kept in GEMM1's header:
+    int32_t epoch;          // such launches completed over this schedule
+    int32_t all_done;       // epoch + 1 once every GEMM1 tile of the running launch is stored
+    int32_t pad2[6];
     int32_t ticket[kMaxGemmWorkgroups][8]; // per workgroup: tiles drawn by its first thread for all of it
 };
 constexpr size_t kTileTableHeaderBytes = 32768;
 constexpr int32_t kTableMagic = 0x4D6F4554;
-constexpr int32_t kNoScheduleError = 0x4E6F5363;
-static_assert(sizeof(TileTableHeader) <= kTileTableHeaderBytes, "header region");
+constexpr int32_t kNoScheduleError = 0x4E6F5363;   // a GEMM step found no tile table for its rows
+constexpr int32_t kDependencyTimeout = 0x44657054; // a wait for rows of the first GEMM ran into its poll limit
+constexpr int kReadyBit = 1 << 30;                 // in a drawn tile word: the tile's rows were complete when it was drawn
+// How a producer tile makes its rows visible to consumers on other XCDs (whose L2 does not snoop this
+// one's): 1 = device-scope stores, written through the L2 (the form that is used); 0 = ordinary stores
+// and a device-scope release, i.e. a write-back of the whole L2, per wavefront and tile (measured: tens
+// of microseconds each, the launch takes twice as long); 2 = ordinary stores and no write-back: NOT
+// coherent, for timing experiments only.
+#ifndef MOE_DEP_STORE_THROUGH
+#define MOE_DEP_STORE_THROUGH 1
+#endif
 
 // Ticket j of an XCD -> position in a stream: each XCD takes runs of `patch` consecutive tiles, so
 // its L2 sees tiles that share weight and activation rows.
@@ -159,16 +171,17 @@ constexpr int part_first(int dist, int parts, int p)
     return s;
 }
 // Loads of a window that are issued after the last load the next barrier has to wait for.  Inside a
-// position the B loads go first, then the A loads; `a_needed` says whether the A loads of the window
-// belong to the same K tile as its B loads (else they belong to a later one and nobody waits yet).
-constexpr int window_tail(int dist_a, int dist_b, int parts, bool a_needed)
+// position the loads of the "near" operand (the one the next barrier needs) go first, then those of
+// the "far" operand; `far_needed` says whether the far loads of the window belong to the same K tile
+// as its near loads (else they belong to a later one and nobody waits yet).
+constexpr int window_tail(int dist_far, int dist_near, int parts, bool far_needed)
 {
     int after = 0;
     for (int p = parts - 1; p >= 0; --p) {
-        if (a_needed && part_loads(dist_a, parts, p) > 0)
+        if (far_needed && part_loads(dist_far, parts, p) > 0)
             return after;
-        after += part_loads(dist_a, parts, p);
-        if (part_loads(dist_b, parts, p) > 0)
+        after += part_loads(dist_far, parts, p);
+        if (part_loads(dist_near, parts, p) > 0)
             return after;
     }
     return after;
@@ -179,12 +192,18 @@ constexpr int window_tail(int dist_a, int dist_b, int parts, bool a_needed)
 // kExtra_ > 0 ("tall"): a tile may carry up to kExtra_ rows beyond its BM, the short remainder of
 // an expert's segment.  Those rows do not pass through LDS: every wavefront keeps one more 32-row
 // block of accumulators and fetches that block's operand straight into registers.
+// kFarB_ (odd rings only): which operand uses the spare unit to run one K tile further ahead: the A
+// rows (false) or the B rows, i.e. the weights (true).  The operand that runs ahead has two K tiles
+// and more to land, the other one about one: the one that runs ahead should be the one that comes
+// from furthest away.
 template <int BM_, int BN_, int WM_, int WN_, bool kSwiglu, int kBK_, int kUnits_, int kDistA_, int kDistB_, int kKind_,
-          int kExtra_ = 0>
+          int kExtra_ = 0, bool kFarB_ = false>
 struct GemmCfg {
     static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, kBK = kBK_, kUnits = kUnits_;
     static constexpr int kDistA = kDistA_, kDistB = kDistB_, kKind = kKind_, kExtra = kExtra_;
     static constexpr bool kTall = kExtra_ > 0;
+    static constexpr bool kFarB = kFarB_;
+    static_assert(!kFarB_ || (kUnits_ % 2 == 1 && BM_ == BN_), "only an odd ring has a unit to spare");
     static_assert(kExtra_ == 0 || (kExtra_ == 32 * WM_ && WM_ == 2 && (BN_ / WN_ / 32) % 2 == 0),
                   "one extra 32-row block per wavefront row, two wavefront rows that can share one block");
     static constexpr int kWaves = WM * WN;
@@ -206,7 +225,7 @@ struct GemmCfg {
     // (A, B) pairs and the ring is even.
     static constexpr int kABytes = BM * kRowBytes, kBBytes = BN * kRowBytes;
     static constexpr int kDepth = kUnits / 2;  // K tiles whose B part fits besides the one in use
-    static constexpr int kAheadA = kUnits % 2; // an odd ring lets the A loads run one tile further ahead
+    static constexpr int kAhead = kUnits % 2;  // an odd ring lets one operand's loads run one tile further ahead
     static constexpr size_t kLdsBytes =
         BM == BN ? (size_t)kUnits * kABytes : (size_t)(kUnits / 2) * (kABytes + kBBytes);
     static constexpr int unit_base(int unit)
@@ -218,10 +237,36 @@ struct GemmCfg {
     static_assert(kWaveM % 32 == 0 && kWaveN % 32 == 0, "wave tile must be 32x32 blocks");
     static_assert(BM % (kGroupRows * kWaves) == 0 && BN % (kGroupRows * kWaves) == 0, "load groups");
     static_assert(!kSwiglu || kBlkN % 2 == 0, "gate and up halves");
-    static_assert(kLoadsPerTile * (kDepth + kAheadA) <= 63, "vmcnt budget");
+    static_assert(kLoadsPerTile * (kDepth + kAhead) <= 63, "vmcnt budget");
 };
 
-// Persistent grouped GEMM.  Main: the geometry of stream 0 (and of everything when there is no
+// What one GEMM needs.  The last five members drive the dependency-driven form, in which both GEMMs of
+// the expert computation run in one launch and a tile of the second starts as soon as the rows it reads
+// have been stored by the first (the role the paper gives its data availability manager, Section IV-C:
+// a table of what each group of thread blocks depends on, counters of what has arrived, and a ready
+// signal to the scheduler - here a counter per row tile in global memory, bumped by the producing
+// wavefronts and polled by the consuming workgroup's first thread).
+struct GemmArgs {
+    const uint16_t *A;
+    int64_t M;
+    int Kdim, Ndim;
+    const uint16_t *B0, *B1;
+    uint16_t *C;
+    TileTableHeader *hdr;
+    const TileEntry *table;
+    int patch;
+    const int32_t *gather_rows;
+    int gather_div;
+    uint32_t gather_bytes;
+    const float *scatter_w;
+    int32_t *ready;            // [M], indexed by a row tile's first row: wavefronts that have stored their part of it
+    TileTableHeader *hdr_dep;  // the producing GEMM's header (epoch, all_done)
+    int32_t ready_per_launch;  // what a row tile's counter gains per launch: wavefronts x column tiles of the producer
+    int64_t wait_limit;        // polls a consumer spends on one row tile before it gives up
+};
+
+// Persistent grouped GEMM, as a function: a kernel runs one of them, or (the dependency-driven expert
+// computation) the two GEMMs one after the other.  Main: the geometry of stream 0 (and of everything when there is no
 // second geometry); Light: the geometry of stream 1, tiles of experts with at most Light::BM rows,
 // or `void`.  Both geometries have the same workgroup size, BN and K tile.
 // kGather: row m of the A operand is row gather_rows[m] / gather_div of `A` (the dispatch's row
@@ -229,17 +274,27 @@ struct GemmCfg {
 // kScatter: the result is not stored as row m of C.  `C` is an fp32 matrix of Ndim columns, and row
 // m of the result, times scatter_w[gather_rows[m]], is added (atomically) to its row
 // gather_rows[m] / gather_div: the combine step done by the epilogue.
-template <class Main, class Light, bool kSwiglu, bool kGather, bool kScatter = false>
-__global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 : 1)) void grouped_gemm_bf16(
-    const uint16_t *__restrict__ A, int64_t M, int Kdim, int Ndim,
-    const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
-    uint16_t *__restrict__ C, TileTableHeader *__restrict__ hdr,
-    const TileEntry *__restrict__ table, int patch,
-    const int32_t *__restrict__ gather_rows, int gather_div, uint32_t gather_bytes,
-    const float *__restrict__ scatter_w)
+// kDep: 0 = plain; 1 = producer: results are stored through to memory and every wavefront bumps its
+// row tile's counter once its stores are acknowledged; 2 = consumer: a tile whose rows were not
+// complete when it was drawn is not prefetched, and its workgroup waits for the counter before loading.
+#if defined(__HIP_DEVICE_COMPILE__) // the body uses device-only types (buffer resources); the host pass only needs the kernels' stubs
+template <class Main, class Light, bool kSwiglu, bool kGather, bool kScatter, int kDep>
+__device__ __forceinline__ void gemm_phase(const GemmArgs &g)
 {
+    const uint16_t *__restrict__ const A = g.A;
+    const int64_t M = g.M;
+    const int Kdim = g.Kdim, Ndim = g.Ndim;
+    const uint16_t *__restrict__ const B0 = g.B0, *__restrict__ const B1 = g.B1;
+    uint16_t *__restrict__ const C = g.C;
+    TileTableHeader *__restrict__ const hdr = g.hdr;
+    const TileEntry *__restrict__ const table = g.table;
+    const int patch = g.patch;
+    const int32_t *__restrict__ const gather_rows = g.gather_rows;
+    const int gather_div = g.gather_div;
+    const uint32_t gather_bytes = g.gather_bytes;
+    const float *__restrict__ const scatter_w = g.scatter_w;
     static_assert(!(kGather && kScatter) && !(kScatter && kSwiglu), "kScatter belongs to the down projection");
-#if defined(__HIP_DEVICE_COMPILE__) // the body uses device-only types (buffer resources); the host pass only needs the stub
+    static_assert(kDep == 0 || (!kGather && !kScatter), "the dependency-driven form is built for the plain GEMMs");
     constexpr bool kTwo = !std::is_void<Light>::value;
     if constexpr (kTwo)
         static_assert(std::conditional_t<kTwo, Light, Main>::kBK == Main::kBK &&
@@ -268,6 +323,11 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
     }
     const int xcd = blockIdx.x % kXcds;
     int32_t *const my_ticket = hdr->ticket[blockIdx.x];
+#ifdef MOE_TRACE_CLOCK
+    // timing build only: shader-clock and 100 MHz stamps of the workgroup's life, left in its ticket words
+    const uint64_t trace_c0 = __builtin_amdgcn_s_memtime(), trace_r0 = __builtin_amdgcn_s_memrealtime();
+    uint32_t trace_ticks[4] = {0, 0, 0, 0}, trace_tiles[4] = {0, 0, 0, 0}; // full, tall, ragged, shallow
+#endif
     const int len0 = hdr->len[0], len1 = hdr->len[1];
     const int slot = (blockIdx.x / kXcds) % 32, ls = hdr->light_slots;
     const bool light_first = ((slot + 1) * ls) / 32 > (slot * ls) / 32;
@@ -293,7 +353,30 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         }
         return -1;
     };
-    auto kind_of = [&](int tile) { return kTwo && tile >= len0 ? 1 : 0; };
+    // a drawn tile travels as a word: -1 = none, else the table entry, plus (consumer) kReadyBit
+    auto entry_of = [](int word) { return word & ~kReadyBit; };
+    auto kind_of = [&](int word) { return kTwo && entry_of(word) >= len0 ? 1 : 0; };
+    // consumer, thread 0 only: were the rows this tile reads complete at the time of the draw?
+    const int32_t dep_epoch1 =
+        kDep != 0 ? __hip_atomic_load(&(kDep == 1 ? hdr : g.hdr_dep)->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1 : 0;
+    const int64_t dep_target = (int64_t)dep_epoch1 * g.ready_per_launch;
+    bool all_done_seen = false;
+    auto rows_complete = [&](int m0) {
+        return (int64_t)__hip_atomic_load(g.ready + m0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= dep_target;
+    };
+    auto with_ready_bit = [&](int tile) {
+        if constexpr (kDep == 2) {
+            if (tile < 0)
+                return tile;
+            if (!all_done_seen)
+                all_done_seen = __hip_atomic_load(&g.hdr_dep->all_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == dep_epoch1;
+            if (!all_done_seen && !rows_complete(table[tile].m0))
+                return tile;
+            return tile | kReadyBit;
+        } else {
+            return tile;
+        }
+    };
     // words 0, 1: the workgroup's first two tiles; words 2..5: two {tile, sequence number} pairs,
     // used in turn, so that a draw stays readable until the draw after the next one is published
     uint32_t seq = 0; // draws published so far
@@ -309,6 +392,7 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
     int cur_t, nxt_t;   // the tile being computed and the next one, as table entries (-1: none)
     int after_next = -1; // the tile after `nxt`, picked up from the ticket slot inside the K loop
     int drawn = -1;      // thread 0: the tile after that
+    bool gave_up = false; // consumer: a wait ran into its poll limit
 
     // ---- everything that depends on the tile geometry.  One call works through the workgroup's
     //      tiles as long as they are of this geometry's kind.
@@ -317,8 +401,10 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
     constexpr int BM = Cfg::BM, WN = Cfg::WN, kBK = Cfg::kBK, kUnits = Cfg::kUnits;
     constexpr int kDistA = Cfg::kDistA, kDistB = Cfg::kDistB;
     constexpr int kChunks = Cfg::kChunks, kRowBytes = Cfg::kRowBytes, kKSteps = Cfg::kKSteps;
-    constexpr int kDepth = Cfg::kDepth, kAheadA = Cfg::kAheadA;
-    constexpr bool kTall = Cfg::kTall;
+    constexpr int kDepth = Cfg::kDepth, kAhead = Cfg::kAhead;
+    constexpr bool kTall = Cfg::kTall, kFarB = Cfg::kFarB;
+    // loads of a window: how far ahead of the tile whose barrier opened it each operand is fetched
+    constexpr int kAheadOfA = kDepth + (kFarB ? 0 : kAhead), kAheadOfB = kDepth + (kFarB ? kAhead : 0);
     const int wm = wave / WN, wn = wave % WN;
 
     // ---- global->LDS loads (buffer_load_dwordx4 ... lds): the lane at 16-byte position p of its
@@ -373,11 +459,11 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         fr_x = fr;
         x_off = ((kGather ? 0 : (BM + wm * 32 + fr) * Kdim) + kg * 8) * 2;
     };
-    // With kDepth + kAheadA K tiles or more per output tile, the loads that would run past the
+    // With kDepth + kAhead K tiles or more per output tile, the loads that would run past the
     // end of a tile's reduction fetch the first K tiles of the workgroup's next tile (if that is
     // of the same kind), so that tile starts with its operands in LDS.  (Shorter reductions
     // start every tile from scratch.)
-    const bool warm = KT >= kDepth + kAheadA;
+    const bool warm = KT >= kDepth + kAhead;
 
     // What the loads of a tile need.  Rows past the end of the segment (and columns past Ndim) lie
     // beyond the byte counts: the bounds check returns zeros for them without touching memory; a
@@ -393,7 +479,7 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
     auto operands_of = [&](int tile) {
         Operands o = {A, B0, 0u, 0u, 0, 0, 0, 0};
         if (tile >= 0) {
-            const TileEntry te = table[tile];
+            const TileEntry te = table[entry_of(tile)];
             const int n0 = (te.n_tile & ((1 << kTileColBits) - 1)) * Cfg::kOutCols;
             o.ext = kTall ? te.n_tile >> kTileColBits : 0;
             const int64_t rows_left = (int64_t)te.m_end - te.m0; // >= 1
@@ -513,45 +599,55 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
             (here ? t : t - KT) * (kBK * 2), 0, Cfg::kKind == 1 ? 2 : 0);
     };
 
-    // ---- the ring.  K tile t keeps its A rows in unit (2t) % kUnits and its B rows in unit
+    // ---- the ring.  K tile t keeps the rows of its "far" operand (the one whose loads run ahead in
+    //      an odd ring: A, or B with kFarB) in unit (2t) % kUnits and those of the other in unit
     //      (2t+1) % kUnits, counting the K tiles of a workgroup's successive output tiles on (when
-    //      `warm`).  `u` below is always the A unit of the K tile being multiplied.
+    //      `warm`).  `u` below is always the far operand's unit of the K tile being multiplied.
     auto wrap = [](int x) { return x >= kUnits ? x - kUnits : x; };
-    auto unit_a = [&](int u, int ahead) { return wrap(u + (2 * ahead) % kUnits); };
-    auto unit_b = [&](int u, int ahead) { return wrap(u + (2 * ahead + 1) % kUnits); };
+    auto unit_a = [&](int u, int ahead) { return wrap(u + (2 * ahead + (kFarB ? 1 : 0)) % kUnits); };
+    auto unit_b = [&](int u, int ahead) { return wrap(u + (2 * ahead + (kFarB ? 0 : 1)) % kUnits); };
 
     // ---- load schedule.  The barrier that ends the reads of K tile t opens a "window": the units
-    //      of tile t are free, and until the next barrier the loads of B(t + kDepth) and of
-    //      A(t + kDepth + kAheadA) are issued, in kKSteps positions: position 0 under the last
+    //      of tile t are free, and until the next barrier the loads of B(t + kAheadOfB) and of
+    //      A(t + kAheadOfA) are issued, in kKSteps positions: position 0 under the last
     //      k-step of tile t, position p under k-step p-1 of tile t+1 (kDistB / kDistA say how many
-    //      loads each position takes; B first, then A).  Spreading them keeps the four wavefronts
-    //      from pushing a whole tile into the memory pipeline in one burst; putting the B loads
-    //      early gives them two to three k-steps to land before the barrier that needs them, and
-    //      the A loads, which are needed one tile later when the ring is odd, fill the rest.
+    //      loads each position takes; inside a position the operand needed sooner goes first).
+    //      Spreading them keeps the four wavefronts from pushing a whole tile into the memory
+    //      pipeline in one burst; the loads of the operand the next barrier needs go early, which
+    //      gives them two to three k-steps to land, and those of the operand that runs ahead in an
+    //      odd ring, needed one tile later, fill the rest.
     static_assert(part_first(kDistA, kKSteps, kKSteps) == Cfg::kAGroups, "A loads of a window");
     static_assert(part_first(kDistB, kKSteps, kKSteps) == Cfg::kBGroups, "B loads of a window");
     auto issue_position = [&](int t, int u, auto pos_tag, auto tail_tag) { // window opened by the barrier of tile t
         constexpr int p = decltype(pos_tag)::value;
+        if constexpr (!kFarB) {
 #pragma unroll
-        for (int g = part_first(kDistB, kKSteps, p); g < part_first(kDistB, kKSteps, p + 1); ++g)
-            load_b_group(t + kDepth, unit_b(u, kDepth), g, tail_tag);
+            for (int g = part_first(kDistB, kKSteps, p); g < part_first(kDistB, kKSteps, p + 1); ++g)
+                load_b_group(t + kAheadOfB, unit_b(u, kAheadOfB), g, tail_tag);
+        }
 #pragma unroll
         for (int g = part_first(kDistA, kKSteps, p); g < part_first(kDistA, kKSteps, p + 1); ++g)
-            load_a_group(t + kDepth + kAheadA, unit_a(u, kDepth + kAheadA), g, tail_tag);
+            load_a_group(t + kAheadOfA, unit_a(u, kAheadOfA), g, tail_tag);
+        if constexpr (kFarB) {
+#pragma unroll
+            for (int g = part_first(kDistB, kKSteps, p); g < part_first(kDistB, kKSteps, p + 1); ++g)
+                load_b_group(t + kAheadOfB, unit_b(u, kAheadOfB), g, tail_tag);
+        }
     };
     auto loads_at = [](int p) { return part_loads(kDistA, kKSteps, p) + part_loads(kDistB, kKSteps, p); };
     // loads that may still be in flight when a barrier needs the next tile complete
-    constexpr int kInFlight = (kDepth - 2) * Cfg::kLoadsPerTile + window_tail(kDistA, kDistB, kKSteps, kAheadA == 0);
+    constexpr int kInFlight = (kDepth - 2) * Cfg::kLoadsPerTile +
+                              (kFarB ? window_tail(kDistB, kDistA, kKSteps, false) : window_tail(kDistA, kDistB, kKSteps, kAhead == 0));
     using tail_yes = std::integral_constant<bool, true>;
     using tail_no = std::integral_constant<bool, false>;
 
     bf16x8 fa[2][Cfg::kBlkM], fb[2][Cfg::kBlkN];
     // `act` = number of this wavefront's 32-row blocks that hold rows of the segment: blocks past
     // the end of a ragged segment are neither read nor multiplied.
-    auto read_frags = [&](int u, int ks, int slot, auto act_tag) { // u = A unit of the tile
+    auto read_frags = [&](int u, int ks, int slot, auto act_tag) { // u = far operand's unit of the tile
         constexpr int kAct = decltype(act_tag)::value;
-        const unsigned char *pa = lds + Cfg::unit_base(u) + (a_off0 ^ (ks << 5));
-        const unsigned char *pb = lds + Cfg::unit_base(wrap(u + 1)) + (b_off0 ^ (ks << 5));
+        const unsigned char *pa = lds + Cfg::unit_base(unit_a(u, 0)) + (a_off0 ^ (ks << 5));
+        const unsigned char *pb = lds + Cfg::unit_base(unit_b(u, 0)) + (b_off0 ^ (ks << 5));
 #pragma unroll
         for (int i = 0; i < kAct; ++i)
             fa[slot][i] = *reinterpret_cast<const bf16x8 *>(pa + i * 32 * kRowBytes);
@@ -661,14 +757,14 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
             MOE_WAIT_VMCNT(kInFlight + (kExt ? kXRegs - 1 : 0)); // my part of tile kt+1 has landed
             lds_barrier();                     // ... and everyone's; the units of tile kt are free
             issue_position(kt, u, std::integral_constant<int, 0>{}, tail_tag);
-            read_frags(unit_a(u, 1), 0, 0, act); // past the last K tile: the next output tile's, read again there
+            read_frags(wrap(u + 2), 0, 0, act); // past the last K tile: the next output tile's, read again there
             mfma_all((kKSteps - 1) & 1, act);
             if constexpr (kExt)
                 mfma_x((kKSteps - 1) & 1, std::integral_constant<int, kKSteps - 1>{}, kt + 1, half_tag{});
             interleave_under_mfma<kMfma, kReads, loads_at(0)>();
-            u = unit_a(u, 1);
+            u = wrap(u + 2);
         };
-        // the last kDepth + kAheadA K tiles look past the end of this tile's reduction
+        // the last kDepth + kAhead K tiles look past the end of this tile's reduction
         uint64_t slot_v = 0; // (sequence number 0: never a published one)
         if constexpr (kExt) {
             // one loop and nothing else between its K tiles, see xa; the next tile is looked up below
@@ -683,7 +779,7 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
                 asm volatile("s_waitcnt vmcnt(0)" : "+v"(d0), "+v"(d1), "+v"(d2), "+v"(d3));
             }
         } else {
-            const int k_split = KT - (kDepth + kAheadA);
+            const int k_split = KT - (kDepth + kAhead);
             if (k_split > 0)
                 ktile(0, tail_no{});
             else
@@ -706,7 +802,7 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         // runs under the epilogue; the tile is published after it.
         drawn = -1;
         if (tid == 0 && after_next >= 0)
-            drawn = fetch_tile();
+            drawn = with_ready_bit(fetch_tile());
 
         // ---- epilogue.  Block (i, j), register r of lane l:
         //      output row    m = i*32 + l%32               (within the wavefront's rows)
@@ -741,6 +837,10 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
                     unsafeAtomicAdd(d.sums + col + t, d.w * v[t]);
+            } else if constexpr (kDep == 1 && MOE_DEP_STORE_THROUGH == 1) {
+                // device-scope store: written through this XCD's L2, which the other XCDs do not snoop
+                const uint64_t o = (uint64_t)pack_bf16x2(v[0], v[1]) | ((uint64_t)pack_bf16x2(v[2], v[3]) << 32);
+                __hip_atomic_store(reinterpret_cast<uint64_t *>(d.crow + col), o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             } else {
                 u32x2 o;
                 o[0] = pack_bf16x2(v[0], v[1]);
@@ -810,18 +910,56 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
                 }
             }
         }
+        if constexpr (kDep == 1 && MOE_DEP_STORE_THROUGH != 0) {
+            // this wavefront's part of the row tile is in memory once its stores are acknowledged
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (lane == 0)
+                __hip_atomic_fetch_add(g.ready + cur.m0, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else if constexpr (kDep == 1) {
+            // The stores went into this XCD's L2, which the other XCDs do not snoop: a device-scope release
+            // (wait for the stores, write the L2's dirty lines back) before the counter is bumped.
+            __hip_atomic_fetch_add(g.ready + cur.m0, lane == 0 ? 1 : 0, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
     };
 
     bool primed = false; // K tile 0 of `cur` is in LDS already
     while (cur_t >= 0 && kind_of(cur_t) == Cfg::kKind) {
         lane_setup();
         // the next tile's first K tiles ride behind this one's last
-        const bool chain = warm && nxt_t >= 0 && kind_of(nxt_t) == Cfg::kKind;
+        const bool chain = warm && nxt_t >= 0 && kind_of(nxt_t) == Cfg::kKind && (kDep != 2 || (nxt_t & kReadyBit));
         nxt = operands_of(chain ? nxt_t : -1);
         if constexpr (kGather)
             gather_lookup(nxt, nxt_row);
         if (!primed) {
             cur = operands_of(cur_t);
+            if constexpr (kDep == 2) {
+                // The rows were not complete when this tile was drawn: wait for them now.  Nothing of the
+                // workgroup is in flight here and LDS is idle, so the first thread polls and tells the
+                // others through LDS.  Every producer tile has been drawn by a workgroup that waits for
+                // nothing, so the wait ends; the poll limit only guards against a broken schedule.
+                if (!(cur_t & kReadyBit)) {
+                    volatile int32_t *const verdict = reinterpret_cast<volatile int32_t *>(lds);
+                    if (tid == 0) {
+                        int64_t polls = 0;
+                        bool ok = rows_complete(cur.m0);
+                        while (!ok && polls++ < g.wait_limit) {
+                            __builtin_amdgcn_s_sleep(32);
+                            ok = rows_complete(cur.m0);
+                        }
+                        if (!ok)
+                            __hip_atomic_store(&hdr->error, kDependencyTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        *verdict = ok ? 1 : 0;
+                    }
+                    __syncthreads();
+                    const bool ok = __builtin_amdgcn_readfirstlane(*verdict) != 0;
+                    __syncthreads();
+                    if (!ok) { // give up: this workgroup's tiles stay undone, the error word says so
+                        cur_t = nxt_t = -1;
+                        gave_up = true;
+                        break;
+                    }
+                }
+            }
             if constexpr (kGather) {
                 gather_lookup(cur, cur_row);
                 gather_offsets(cur_row);
@@ -831,24 +969,31 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
             // window before it; K tile 0 landed
             u = 0;
 #pragma unroll
-            for (int t = 0; t + 1 < kDepth + kAheadA; ++t) {
+            for (int t = 0; t + 1 < kDepth + kAhead; ++t) {
+                const bool both = t + 1 < kDepth; // else only the operand that runs ahead
+                if (both || !kFarB) {
 #pragma unroll
-                for (int g = 0; g < Cfg::kAGroups; ++g)
-                    load_a_group(t, (2 * t) % kUnits, g, tail_yes{});
-                if (t + 1 < kDepth) {
+                    for (int g = 0; g < Cfg::kAGroups; ++g)
+                        load_a_group(t, unit_a((2 * t) % kUnits, 0), g, tail_yes{});
+                }
+                if (both || kFarB) {
 #pragma unroll
                     for (int g = 0; g < Cfg::kBGroups; ++g)
-                        load_b_group(t, (2 * t + 1) % kUnits, g, tail_yes{});
+                        load_b_group(t, unit_b((2 * t) % kUnits, 0), g, tail_yes{});
                 }
             }
             issue_position(-1, kUnits - 2, std::integral_constant<int, 0>{}, tail_yes{});
-            // in flight after B(0): tiles 1 .. kDepth-2, the A rows that run ahead, position 0
-            MOE_WAIT_VMCNT((kDepth - 2) * Cfg::kLoadsPerTile + kAheadA * Cfg::kAGroups + loads_at(0));
+            // in flight after K tile 0: tiles 1 .. kDepth-2, the rows that run ahead, position 0
+            MOE_WAIT_VMCNT((kDepth - 2) * Cfg::kLoadsPerTile + kAhead * (kFarB ? Cfg::kBGroups : Cfg::kAGroups) + loads_at(0));
             lds_barrier();
         }
         // rows of the segment inside this wavefront's part of the tile -> active 32-row blocks
         const int64_t rows = (int64_t)cur.m_end - ((int64_t)cur.m0 + wm * Cfg::kWaveM);
         const int active = rows <= 0 ? 0 : (rows >= Cfg::kWaveM ? Cfg::kBlkM : (int)((rows + 31) / 32));
+#ifdef MOE_TRACE_CLOCK
+        const uint64_t trace_t0 = __builtin_amdgcn_s_memrealtime();
+        const int trace_kind = Cfg::kKind == 1 ? 3 : (cur.ext > 0 ? 1 : (cur.m_end - cur.m0 >= Cfg::BM ? 0 : 2));
+#endif
         using ext_no = std::integral_constant<int, 0>;
         using ext_half = std::integral_constant<int, kTall ? 1 : 0>;
         using ext_full = std::integral_constant<int, kTall ? 2 : 0>;
@@ -868,6 +1013,10 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
         else
             run_tile(std::integral_constant<int, (Cfg::kBlkM > 3 ? 3 : 1)>{}, ext_no{});
 
+#ifdef MOE_TRACE_CLOCK
+        trace_ticks[trace_kind] += (uint32_t)(__builtin_amdgcn_s_memrealtime() - trace_t0);
+        trace_tiles[trace_kind] += 1;
+#endif
         // Thread 0 leaves the tile it drew before the epilogue in the other slot under the next
         // sequence number; the others look there after the next tile's first barrier.
         ++seq;
@@ -893,35 +1042,58 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
 
     // ---- the workgroup's first three tiles.  The words still hold what an earlier launch left
     //      there, so these stores have to be in memory before anyone looks.
-    seq = 1;
-    if (tid == 0) {
-        int t = 0;
+    //      A consumer phase with only a few tiles per workgroup draws one tile at a time instead:
+    //      its workgroups arrive one by one as they run out of producer tiles, and the early ones
+    //      would take three tiles each where two are everybody's share.  Such a tile starts cold
+    //      (no operands fetched behind its predecessor), which long or few tiles can afford.
+    const bool one_at_a_time = kDep == 2 && len0 + len1 < 4 * (int)gridDim.x;
+    bool again;
+    do {
+        seq = 1;
+        if (tid == 0) {
+            int t = 0;
 #pragma unroll 1
-        for (int w = 0; w < 3; ++w) {
-            t = t >= 0 ? fetch_tile() : -1;
-            if (w < 2)
-                __hip_atomic_store(my_ticket + w, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            else
-                publish(t);
+            for (int w = 0; w < 3; ++w) {
+                t = t >= 0 && (w == 0 || !one_at_a_time) ? with_ready_bit(fetch_tile()) : -1;
+                if (w < 2)
+                    __hip_atomic_store(my_ticket + w, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                else
+                    publish(t);
+            }
         }
-    }
-    MOE_WAIT_VMCNT(0);
-    __syncthreads();
-    cur_t = __builtin_amdgcn_readfirstlane(
-        __hip_atomic_load(my_ticket + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    nxt_t = __builtin_amdgcn_readfirstlane(
-        __hip_atomic_load(my_ticket + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    while (cur_t >= 0) {
-        if constexpr (kTwo) {
-            if (kind_of(cur_t) == 1)
-                engine(std::conditional_t<kTwo, Light, Main>{});
-            else
+        MOE_WAIT_VMCNT(0);
+        __syncthreads();
+        cur_t = __builtin_amdgcn_readfirstlane(
+            __hip_atomic_load(my_ticket + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        nxt_t = __builtin_amdgcn_readfirstlane(
+            __hip_atomic_load(my_ticket + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        again = one_at_a_time && cur_t >= 0;
+        while (cur_t >= 0) {
+            if constexpr (kTwo) {
+                if (kind_of(cur_t) == 1)
+                    engine(std::conditional_t<kTwo, Light, Main>{});
+                else
+                    engine(Main{});
+            } else {
                 engine(Main{});
-        } else {
-            engine(Main{});
+            }
+        }
+        MOE_WAIT_VMCNT(0);
+    } while (again && !gave_up);
+#ifdef MOE_TRACE_CLOCK
+    if (tid == 0) {
+        my_ticket[6] = (int32_t)(__builtin_amdgcn_s_memtime() - trace_c0);
+        my_ticket[7] = (int32_t)(__builtin_amdgcn_s_memrealtime() - trace_r0);
+        // per tile kind: 100 MHz ticks and tiles, behind the table's last entry (the table must have room)
+        uint32_t *out = reinterpret_cast<uint32_t *>(const_cast<TileEntry *>(table) + len0 + len1) + blockIdx.x * 8;
+        for (int k = 0; k < 4; ++k) {
+            out[2 * k] = trace_ticks[k];
+            out[2 * k + 1] = trace_tiles[k];
         }
     }
-    MOE_WAIT_VMCNT(0);
+#endif
+    if constexpr (kDep != 0)
+        __syncthreads(); // every wavefront of the workgroup has stored (and signalled) what it had to
     // the last workgroup to leave resets the counters for the next launch over this table
     if (tid == 0) {
         if (__hip_atomic_fetch_add(&hdr->done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1) {
@@ -930,8 +1102,36 @@ __global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 :
                 for (int x = 0; x < kXcds; ++x)
                     __hip_atomic_store(&hdr->next[s][x], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(&hdr->done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if constexpr (kDep == 1) // all producer tiles are in memory: consumers need not look at counters any more
+                __hip_atomic_store(&hdr->all_done, dep_epoch1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if constexpr (kDep == 2) // the launch is over: the next one counts from here
+                __hip_atomic_store(&g.hdr_dep->epoch, dep_epoch1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
+}
+#endif // __HIP_DEVICE_COMPILE__
+
+// One GEMM per launch.
+template <class Main, class Light, bool kSwiglu, bool kGather, bool kScatter = false>
+__global__ __launch_bounds__(Main::kThreads, (Main::kLdsBytes <= 80 * 1024 ? 2 : 1)) void grouped_gemm_bf16(GemmArgs g)
+{
+    static_assert(!(kGather && kScatter) && !(kScatter && kSwiglu), "kScatter belongs to the down projection");
+#if defined(__HIP_DEVICE_COMPILE__) // the body uses device-only types (buffer resources); the host pass only needs the stub
+    gemm_phase<Main, Light, kSwiglu, kGather, kScatter, 0>(g);
+#endif
+}
+
+// Both GEMMs of the expert computation in one launch: a workgroup works through the tiles of the first
+// (gate/up projection with the activation) and, when none is left to draw, goes on to those of the
+// second (down projection), each of which waits for its own rows only.  The tail of the first GEMM and
+// the head of the second overlap, and there is one launch instead of two.
+template <class Main1, class Light1, class Main2, class Light2>
+__global__ __launch_bounds__(Main1::kThreads, 1) void grouped_ffn_bf16(GemmArgs g1, GemmArgs g2)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    gemm_phase<Main1, Light1, true, false, false, 1>(g1);
+    __syncthreads(); // the ring is drained (every path out of a phase waits for its loads); LDS changes hands
+    gemm_phase<Main2, Light2, false, false, false, 2>(g2);
 #endif
 }
 

@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
                           "moe_dispatch_layout_arrival", "moe_dispatch_layout_static",
                           "moe_permute", "moe_grouped_ffn", "moe_combine",
                           "moe_ffn_schedule", "moe_ffn_gate_up", "moe_ffn_gate_up_gather", "moe_ffn_down",
-                          "moe_ffn_down_combine", "moe_ffn_status"}
+                          "moe_ffn_down_combine", "moe_ffn_status", "moe_ffn_gate_up_down"}
     lib = ctypes.CDLL(hub.lib_path()) if os.path.exists(hub.lib_path()) else hub.load_library()
     for n in names:
         assert hasattr(lib, n), n

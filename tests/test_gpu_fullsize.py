@@ -274,6 +274,32 @@ def test_mixtral_shape_at_small_token_counts(G, N):
     G.check_close(G.host(out), o_all, 2e-2, 4e-3, what="combine, all tokens")
 
 
+def test_full_ffn_in_one_launch_equals_two_launches(G, S):
+    """At full size, in the configuration bench.py times: moe_ffn_gate_up_down (a down-projection tile starts
+    when its rows have arrived) gives the y of moe_ffn_gate_up + moe_ffn_down, bit for bit, on two launches
+    over one schedule."""
+    import torch
+    import paper_2605_05888_amd as hub
+    s = S
+    cfg = s["cfg"]
+    El = s["E_local"]
+    M, H = s["xp"].shape
+    seg = s["lay"]["expert_offsets"][:El + 1].contiguous()
+    ws = G.ws_tensor(hub.workspace_bytes(hub.OP_GROUPED_FFN, N=M, H=H, E=El, F=cfg.F, dtype=hub.BF16))
+    hub.moe_ffn_schedule(hub.BF16, M, H, cfg.F, seg, ws)
+    y0 = torch.zeros((M, H), dtype=torch.bfloat16, device="cuda:0")
+    hub.moe_ffn_gate_up(s["xp"], seg, s["W"][0], s["W"][1], ws)
+    hub.moe_ffn_down(seg, s["W"][2], y0, ws)
+    for _ in range(2):
+        y = torch.zeros((M, H), dtype=torch.bfloat16, device="cuda:0")
+        ws[:M * cfg.F * 2].zero_()
+        hub.moe_ffn_gate_up_down(s["xp"], seg, *s["W"], y, ws)
+        hub.moe_ffn_status(hub.BF16, M, H, cfg.F, El, ws)
+        assert torch.equal(y, y0)
+        del y
+    assert bool(y0.any())
+
+
 def test_full_gate_up_with_fused_gather_is_bit_identical(G, S):
     """At full size: GEMM1 fetching its rows from x through row_of_slot leaves the same activation in
     the workspace as GEMM1 over the materialised xp (whose sampled rows the test above checks)."""

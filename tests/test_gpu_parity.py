@@ -377,6 +377,99 @@ def test_ffn_steps_rerun_after_one_schedule(G):
         assert G.host(y).tobytes() == ref
 
 
+def _ffn_three_ways(G, cfg, seg, launches=3):
+    """y of moe_ffn_gate_up + moe_ffn_down, and of `launches` runs of moe_ffn_gate_up_down over one schedule."""
+    import moe_inputs.device as mid
+    import torch
+    import paper_2605_05888_amd as hub
+    M, H, F, E = cfg.N, cfg.H, cfg.F, cfg.E
+    xp = mid.to_device(mi.host_tensor(cfg, mi.STREAM_X))
+    Wg, Wu, Wd = (mid.to_device(mi.host_tensor(cfg, s)) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    dseg = mid.to_device(seg)
+    ws = torch.zeros(hub.workspace_bytes(hub.OP_GROUPED_FFN, N=M, H=H, E=E, F=F), dtype=torch.uint8, device="cuda:0")
+    hub.moe_ffn_schedule(hub.BF16, M, H, F, dseg, ws)
+    y0 = torch.zeros((M, H), dtype=torch.bfloat16, device="cuda:0")
+    hub.moe_ffn_gate_up(xp, dseg, Wg, Wu, ws)
+    hub.moe_ffn_down(dseg, Wd, y0, ws)
+    ys = []
+    for _ in range(launches):
+        y = torch.zeros((M, H), dtype=torch.bfloat16, device="cuda:0")
+        ws[:M * F * 2].zero_()                                   # the activation of the run before must not help
+        hub.moe_ffn_gate_up_down(xp, dseg, Wg, Wu, Wd, y, ws)
+        ys.append(y)
+    hub.moe_ffn_status(hub.BF16, M, H, F, E, ws)
+    return G.host(y0), [G.host(y) for y in ys]
+
+
+@pytest.mark.parametrize("M,H,F,E,dtype,empty", [c for c in FFN_CASES if c[4] == mi.BF16])
+def test_both_gemms_in_one_launch_give_the_bits_of_two_launches(G, M, H, F, E, dtype, empty):
+    """The dependency-driven form (tiles of the down projection start as their rows arrive) against the two
+    separate launches: same bits, also when launched again over the same schedule (the arrival counters
+    count on from launch to launch)."""
+    import dataclasses
+    cfg = dataclasses.replace(mi.CONFIGS["tiny"], N=M, H=H, F=F, E=E, K=1, dtype=dtype, seed=21)
+    _say("ffn in one launch", cfg)
+    seg = _segments(np.random.default_rng(M), M, E, empty)
+    y0, ys = _ffn_three_ways(G, cfg, seg)
+    assert y0.any()
+    for y in ys:
+        assert np.array_equal(y, y0)
+
+
+def test_one_launch_ffn_with_many_more_tiles_than_workgroups(G):
+    """Several rounds of tiles per workgroup in both GEMMs (about 1500 and 700 tiles on 256 workgroups), big,
+    tall, ragged and shallow tiles mixed: down-projection tiles are drawn while gate/up tiles still run."""
+    import dataclasses
+    rng = np.random.default_rng(99)
+    rows = [int(r) for r in rng.choice([3, 40, 64, 65, 200, 256, 270, 300, 512, 530, 777], size=48)]
+    M = sum(rows)
+    cfg = dataclasses.replace(mi.CONFIGS["tiny"], N=M, H=512, F=896, E=len(rows), K=1, dtype=mi.BF16, seed=61)
+    _say("ffn in one launch, many tiles", rows)
+    seg = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    y0, ys = _ffn_three_ways(G, cfg, seg, launches=4)
+    for y in ys:
+        assert np.array_equal(y, y0)
+    xp = mi.host_tensor(cfg, mi.STREAM_X)
+    Wg, Wu, Wd = (mi.host_tensor(cfg, s) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    sample = np.unique(np.concatenate([seg[:-1][np.diff(seg) > 0], seg[1:][np.diff(seg) > 0] - 1,
+                                       rng.integers(0, M, size=200)]))
+    G.check_close(ys[0][sample], oracle.ffn_rows(xp, seg, Wg, Wu, Wd, rows=sample), 2e-2, 1e-2, what="one-launch ffn")
+
+
+def test_one_launch_ffn_gives_up_at_its_poll_limit_and_says_so(G):
+    """The bounded wait, forced from the host: one row tile, 300 gate/up column tiles on 256 workgroups, so
+    the down-projection tiles are drawn while the second round of gate/up tiles has not even started, and a
+    limit of one poll is reached.  The kernel must exit normally, the call returns MOE_OK, and
+    moe_ffn_status reports the state; a normal launch afterwards is complete and correct."""
+    import moe_inputs.device as mid
+    import dataclasses
+    import torch
+    import paper_2605_05888_amd as hub
+    M, H, F, E = 200, 512, 128 * 300, 1
+    cfg = dataclasses.replace(mi.CONFIGS["tiny"], N=M, H=H, F=F, E=E, K=1, dtype=mi.BF16, seed=62)
+    _say("ffn in one launch, poll limit", cfg)
+    xp = mid.to_device(mi.host_tensor(cfg, mi.STREAM_X))
+    Wg, Wu, Wd = (mid.to_device(mi.host_tensor(cfg, s)) for s in (mi.STREAM_W_GATE, mi.STREAM_W_UP, mi.STREAM_W_DOWN))
+    dseg = mid.to_device(np.array([0, M], np.int32))
+    ws = torch.zeros(hub.workspace_bytes(hub.OP_GROUPED_FFN, N=M, H=H, E=E, F=F), dtype=torch.uint8, device="cuda:0")
+    hub.moe_ffn_schedule(hub.BF16, M, H, F, dseg, ws)
+    y = torch.zeros((M, H), dtype=torch.bfloat16, device="cuda:0")
+    hub.moe_ffn_gate_up_down(xp, dseg, Wg, Wu, Wd, y, ws, wait_limit=1)
+    torch.cuda.synchronize()                                     # the kernel has exited
+    with pytest.raises(hub.MoEHubError) as err:
+        hub.moe_ffn_status(hub.BF16, M, H, F, E, ws)
+    assert err.value.code == -5 and "waiting" in str(err.value)
+    hub.moe_ffn_schedule(hub.BF16, M, H, F, dseg, ws)            # clears the word and the counters
+    y2 = torch.zeros((M, H), dtype=torch.bfloat16, device="cuda:0")
+    hub.moe_ffn_gate_up_down(xp, dseg, Wg, Wu, Wd, y2, ws)
+    hub.moe_ffn_status(hub.BF16, M, H, F, E, ws)
+    y3 = torch.zeros((M, H), dtype=torch.bfloat16, device="cuda:0")
+    hub.moe_ffn_gate_up(xp, dseg, Wg, Wu, ws)
+    hub.moe_ffn_down(dseg, Wd, y3, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, y3) and bool(y2.any())
+
+
 @pytest.mark.parametrize("name", list(SMALL))
 def test_gate_up_with_fused_gather_equals_permute_then_gate_up(G, name):
     """GEMM1 fetching its rows through row_of_slot from x gives the bits of permute + GEMM1; the whole
