@@ -133,10 +133,21 @@ __global__ __launch_bounds__(kWave *kRouteWaves) void router_logits(
 // the buffer bounds check; adding a zero product never changes a partial sum (partials start
 // at +0 and can never become -0), so the result is the R64 sum bit for bit.
 // ------------------------------------------------------------------------
+// MOE_ROUTER_MFMA: 1 = the tile is computed on the matrix cores (router_logits_mfma), 0 = on the vector
+// ALUs (router_logits_tiled); same bits either way.
+#ifndef MOE_ROUTER_MFMA
+#define MOE_ROUTER_MFMA 1
+#endif
 constexpr int kRtTok = 8;        // tokens per wavefront
 constexpr int kRtExp = 16;       // experts per workgroup
 constexpr int kRtK = 128;        // K tile
-constexpr int kRtWaves = 4;
+#ifndef MOE_RT_WAVES
+#define MOE_RT_WAVES 4
+#endif
+constexpr int kRtWaves = MOE_RT_WAVES;
+#ifndef MOE_RT_STAGES
+#define MOE_RT_STAGES 2
+#endif
 
 __device__ __forceinline__ int rt_key(int r) { return (((r >> 1) ^ (r >> 3)) & 1) | ((r >> 1) & 2); }
 
@@ -291,6 +302,188 @@ __global__ __launch_bounds__(kWave *kRtWaves) void router_logits_tiled(
 #endif
 }
 
+// ------------------------------------------------------------------------
+// The same tile on the matrix cores, without giving up the order of the sum.  v_mfma_f32_4x4x1_16B_f32
+// multiplies sixteen independent 4x1 by 1x4 pairs: with a reduction length of ONE every output is
+// exactly one fused multiply-add, d = fma(a, b, c) (checked bit for bit against fmaf, signed zeros and
+// subnormal products included), so nothing about the summation order is left to the hardware - and
+// the instruction retires 256 of them in 8 cycles, twice what the vector ALU does without packed
+// arithmetic.  The sixteen blocks of an instruction are sixteen different partial sums of R64:
+//   lane (blk = lane / 4, c = lane % 4), instruction (p, q, g):   partial l = 4 blk + g
+//     a operand: x[token 4p + c, h]          h = 64 step + l
+//     b operand: W_r[h, expert 4c + q]
+//     result register r:  partial l of (token 4p + r, expert 4c + q)
+// so a lane carries the same 128 accumulators as in the vector form, but now for all 8 tokens x 16
+// experts x 4 partials (g), and every K step of 64 columns is 32 instructions instead of 128.
+// LDS: the W_r tile keeps row h = 64 sub + 4 blk + g at row slot 64 sub + 16 g + blk (the loads
+// gather it that way), so the 16-byte read of lane (blk, c) for a given g - experts 4c .. 4c + 3, the
+// four q - is linear in the lane number; the x values of a lane for the four g are 4 consecutive
+// elements of one token row.  The folding rounds s = 32, 16, 8, 4 run between lanes (blk bits), as a
+// halving exchange; s = 2, 1 (g bits) inside the lane.
+// ------------------------------------------------------------------------
+template <int kHalf, int kXor>
+__device__ __forceinline__ void fold_lanes(float *v, bool upper)
+{
+#pragma unroll
+    for (int i = 0; i < kHalf; ++i) {
+        float keep = upper ? v[i + kHalf] : v[i];
+        float send = upper ? v[i] : v[i + kHalf];
+        v[i] = keep + __shfl_xor(send, kXor);
+    }
+}
+
+template <bool kBf16>
+__global__ __launch_bounds__(kWave *kRtWaves, 2) void router_logits_mfma(
+    const void *__restrict__ x, int64_t N, int H, const float *__restrict__ W_r,
+    const float *__restrict__ bias, int E, float *__restrict__ logits)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int kXb = kBf16 ? 2 : 4;                  // bytes per x element
+    constexpr int kXRow = kRtK * kXb;                   // bytes of one token row in a tile
+    constexpr int kXTile = kRtTok * kXRow;              // per wavefront
+    constexpr int kWTile = kRtK * kRtExp * 4;           // 8 KiB
+    constexpr int kStage = kWTile + kRtWaves * kXTile;
+    constexpr int kXLoads = kXTile / 1024;              // per wavefront per tile
+    constexpr int kWLoads = kWTile / 1024 / kRtWaves;   // per wavefront per tile
+    static_assert(kRtTok == 8 && kRtExp == 16 && kRtK == 128, "the index arithmetic below");
+    constexpr int kStages = MOE_RT_STAGES;               // LDS ring: the loads run kStages - 1 tiles ahead
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[kStages * kStage];
+    const int lane = threadIdx.x % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int e0 = blockIdx.x * kRtExp;
+    const int64_t n0 = ((int64_t)blockIdx.y * kRtWaves + wave) * kRtTok;
+    const int blk = lane / 4, c = lane % 4;
+
+    // W_r: load instruction k of a tile fills row slots 16k .. 16k + 15, i.e. (sub, g) = (k / 4, k % 4):
+    // lane (blk', chunk) fetches chunk `chunk` of row 64 sub + 4 blk' + g
+    int w_off[kWLoads];
+#pragma unroll
+    for (int gl = 0; gl < kWLoads; ++gl) {
+        const int k = wave * kWLoads + gl;
+        const int r = 64 * (k / 4) + 4 * blk + (k % 4);
+        w_off[gl] = (r * E + c * 4) * 4;
+    }
+    const int64_t n_left = N - n0;
+    constexpr int kLanesPerRow = kXRow / 16;
+    int x_off[kXLoads];
+#pragma unroll
+    for (int gl = 0; gl < kXLoads; ++gl) {
+        const int t = gl * (kWave / kLanesPerRow) + lane / kLanesPerRow;
+        x_off[gl] = (t * H + (lane % kLanesPerRow) * (16 / kXb)) * kXb;
+    }
+    // (the K tile's position goes into the resources, see router_logits_tiled)
+    auto clamp32 = [](int64_t b) { return (unsigned)(b < 0 ? 0 : (b > 0xFFFFFFFFll ? 0xFFFFFFFFll : b)); };
+    auto issue = [&](int kt) {
+        unsigned char *st = lds + (kt % kStages) * kStage;
+        const int k0 = kt * kRtK;
+        const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float *>(W_r + (int64_t)k0 * E + e0), 0, clamp32(k0 < H ? ((int64_t)(H - k0) * E - e0) * 4 : 0),
+            0x00020000);
+        const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<unsigned char *>(static_cast<const unsigned char *>(x) + (n0 * H + k0) * kXb), 0,
+            clamp32(n_left > 0 && k0 < H ? (n_left * H - k0) * kXb : 0), 0x00020000);
+#pragma unroll
+        for (int gl = 0; gl < kWLoads; ++gl)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rs_w, (__attribute__((address_space(3))) void *)(st + (wave * kWLoads + gl) * 1024), 16,
+                w_off[gl], 0, 0, 0);
+#pragma unroll
+        for (int gl = 0; gl < kXLoads; ++gl)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rs_x, (__attribute__((address_space(3))) void *)(st + kWTile + wave * kXTile + gl * 1024), 16,
+                x_off[gl], 0, 0, 0);
+    };
+
+    // acc[((p * 4 + q) * 4 + g)][r]
+    f32x4 acc[2 * 4 * 4];
+#pragma unroll
+    for (int i = 0; i < 32; ++i)
+        acc[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+    const int KT = (H + kRtK - 1) / kRtK;
+    // (tiles past the last one are issued too: their resources hold no bytes, so they fetch nothing and
+    // the number of loads in flight stays what the wait below counts on)
+#pragma unroll
+    for (int t = 0; t + 1 < kStages; ++t)
+        issue(t);
+    for (int kt = 0; kt < KT; ++kt) {
+        // all but the loads of the kStages - 2 tiles after kt have landed (own loads)
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (((kStages - 2) * (kWLoads + kXLoads)) & 15) |
+                                   ((((kStages - 2) * (kWLoads + kXLoads)) >> 4) << 14));
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();       // ... and everyone's; tile kt-1 is no longer read
+        asm volatile("" ::: "memory");
+        issue(kt + kStages - 1);
+        const unsigned char *st = lds + (kt % kStages) * kStage;
+        const unsigned char *xs = st + kWTile + wave * kXTile;
+#pragma unroll
+        for (int sub = 0; sub < kRtK / kWave; ++sub) {
+            // b operands: for every g the four q of this lane's expert chunk
+            f32x4 wv[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                wv[g] = *reinterpret_cast<const f32x4 *>(st + (64 * sub + 16 * g + blk) * 64 + c * 16);
+            // a operands: for p = 0, 1 the four g of token 4p + c
+            float xv[2][4];
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const unsigned char *px = xs + (4 * p + c) * kXRow + (64 * sub + 4 * blk) * kXb;
+                if (kBf16) {
+                    const u32x2 raw = *reinterpret_cast<const u32x2 *>(px);
+                    xv[p][0] = __uint_as_float(raw[0] << 16);
+                    xv[p][1] = __uint_as_float(raw[0] & 0xFFFF0000u);
+                    xv[p][2] = __uint_as_float(raw[1] << 16);
+                    xv[p][3] = __uint_as_float(raw[1] & 0xFFFF0000u);
+                } else {
+                    const f32x4 raw = *reinterpret_cast<const f32x4 *>(px);
+                    xv[p][0] = raw[0], xv[p][1] = raw[1], xv[p][2] = raw[2], xv[p][3] = raw[3];
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        acc[(p * 4 + q) * 4 + g] =
+                            __builtin_amdgcn_mfma_f32_4x4x1f32(xv[p][g], wv[g][q], acc[(p * 4 + q) * 4 + g], 0, 0, 0);
+        }
+    }
+
+    // Fold.  v index bits, most significant first: p, q (2), r (2), g (2).  The rounds s = 32, 16, 8, 4
+    // of R64 pair partials that differ in a blk bit, i.e. lanes that differ in bit 5, 4, 3, 2; each
+    // halves what a lane keeps (by p, q.hi, q.lo, r.hi).  Left: r.lo x g, and s = 2, 1 pair g.
+    float v[128];
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    v[((p * 4 + q) * 4 + r) * 4 + g] = acc[(p * 4 + q) * 4 + g][r];
+    fold_lanes<64, 32>(v, lane & 32);
+    fold_lanes<32, 16>(v, lane & 16);
+    fold_lanes<16, 8>(v, lane & 8);
+    fold_lanes<8, 4>(v, lane & 4);
+    const int p_keep = (lane >> 5) & 1, q_keep = (lane >> 3) & 3, r_hi = (lane >> 2) & 1;
+#pragma unroll
+    for (int rl = 0; rl < 2; ++rl) {
+        const float *u = v + rl * 4;
+        const float w0 = u[0] + u[2], w1 = u[1] + u[3]; // s = 2
+        float val = w0 + w1;                             // s = 1
+        const int64_t n = n0 + 4 * p_keep + 2 * r_hi + rl;
+        const int e = e0 + 4 * c + q_keep;
+        if (n < N && e < E) {
+            if (bias)
+                val = val + bias[e];
+            logits[n * E + e] = val;
+        }
+    }
+#endif
+}
+
 // (value, index) order of the selection: larger logit first, equal logits to the lower index.
 __device__ __forceinline__ bool better(float va, int ia, float vb, int ib)
 {
@@ -377,12 +570,21 @@ int launch_route(const void *x, int dtype, int64_t N, int64_t H, const float *W_
     const dim3 block(kWave * kRouteWaves);
     if (E % 4 == 0 && H * (int64_t)E * 4 < ((int64_t)1 << 31) && H * 8 * 4 < ((int64_t)1 << 31)) {
         const dim3 grid((unsigned)ceil_div(E, kRtExp), (unsigned)ceil_div(N, (int64_t)kRtTok * kRtWaves));
+#if MOE_ROUTER_MFMA
+        if (dtype == MOE_BF16)
+            hipLaunchKernelGGL(router_logits_mfma<true>, grid, dim3(kWave * kRtWaves), 0, st, x, N, (int)H, W_r,
+                               bias, E, logits);
+        else
+            hipLaunchKernelGGL(router_logits_mfma<false>, grid, dim3(kWave * kRtWaves), 0, st, x, N, (int)H, W_r,
+                               bias, E, logits);
+#else
         if (dtype == MOE_BF16)
             hipLaunchKernelGGL(router_logits_tiled<true>, grid, dim3(kWave * kRtWaves), 0, st, x, N, (int)H, W_r,
                                bias, E, logits);
         else
             hipLaunchKernelGGL(router_logits_tiled<false>, grid, dim3(kWave * kRtWaves), 0, st, x, N, (int)H, W_r,
                                bias, E, logits);
+#endif
     } else {
         const dim3 grid1((unsigned)ceil_div(N, (int64_t)kTok * kRouteWaves), (unsigned)ceil_div(E, kExp));
         if (dtype == MOE_BF16)
