@@ -61,8 +61,8 @@ def parse_args():
     ap.add_argument("--tokens", type=int, default=0, help="override the workload's token count")
     ap.add_argument("--zipf", type=float, default=-1.0,
                     help="override the Zipf exponent of expert popularity (0 = uniform)")
-    ap.add_argument("--graph", action="store_true",
-                    help="also time the step replayed from a HIP graph (one graph of all buffer sets' steps)")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip the HIP-graph replay of the step (one graph of all buffer sets' steps)")
     ap.add_argument("--nbuf", type=int, default=0, help="activation buffer sets rotated per step (0 = auto)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target time of the oracle sample (0 = skip)")
     return ap.parse_args()
@@ -275,13 +275,53 @@ def summarise(cfg, layer, ms_per_step, us):
     }
 
 
+def graph_replay(layer, steps):
+    """The same steps captured once in a HIP graph and replayed: what a serving loop would do with a
+    launch-bound layer.  Every replay is checked against the eager result (the kernels are deterministic, so
+    bit for bit), with eager work and synchronisation between the replays."""
+    import torch
+    N = layer.cfg.N
+    for i in range(len(layer.sets)):
+        layer.step(i)
+    eager_out = [st["out"].clone() for st in layer.sets]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        for i in range(len(layer.sets)):
+            layer.step(i)                      # warm every buffer set on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(len(layer.sets)):
+                layer.step(i)
+    torch.cuda.current_stream().wait_stream(side)
+    reps = max(1, steps // len(layer.sets))
+    same = True
+    for rnd in range(3):
+        for st in layer.sets:
+            st["out"].zero_()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        same = same and all(torch.equal(st["out"], e) for st, e in zip(layer.sets, eager_out))
+        layer.step(0)
+    torch.cuda.synchronize()
+    g_ms = (t1 - t0) * 1e3 / (reps * len(layer.sets))
+    del graph
+    return {"ms_per_step": g_ms, "tokens_per_s": N / (g_ms * 1e-3), "steps_per_graph": len(layer.sets),
+            "replays_timed": reps, "matches_eager_bitwise": bool(same)}
+
+
 def pick_nbuf(cfg, nbuf_arg):
     N, H, K, F, b = cfg.N, cfg.H, cfg.K, cfg.F, cfg.elt_bytes
     act_bytes = (2 * N * H + 2 * N * K * H + N * K * F) * b
     return nbuf_arg or (4 if act_bytes < (1 << 30) else 1)   # rotate small working sets out of the 256 MB cache
 
 
-def short_run(name, cfg, steps, warmup, nbuf_arg):
+def short_run(name, cfg, steps, warmup, nbuf_arg, graph=True):
     """One workload measured in short (the entries of `also` and of the sweeps)."""
     import torch
     nbuf = pick_nbuf(cfg, nbuf_arg)
@@ -292,6 +332,9 @@ def short_run(name, cfg, steps, warmup, nbuf_arg):
     if out["dtype"] == "bf16":
         o_ms, o_us = time_layer(layer, steps, min(3, warmup), one_launch=True)
         out["ffn_one_launch"] = {"ms_per_step": o_ms, "ffn_us": o_us["ffn_gate_up"]}
+    if graph:
+        g = graph_replay(layer, steps)
+        out["graph"] = {k: g[k] for k in ("ms_per_step", "tokens_per_s", "matches_eager_bitwise")}
     out["config"] = {"workload": f"{name}: {WORKLOAD_TEXT.get(name, name)}", "N": cfg.N, "H": cfg.H, "E": cfg.E,
                      "K": cfg.K, "F": cfg.F, "G": cfg.G, "activation_buffer_sets": nbuf}
     del layer
@@ -431,39 +474,8 @@ def main():
                 "down_and_combine_us": s_us["ffn_down"],
                 "down_plus_combine_us_unfused": us["ffn_down"] + us["combine"]}
             layer.sums = None
-    if args.graph:
-        # The same steps captured once and replayed: what a serving loop would do with a launch-bound layer.
-        # Every replay is checked against the eager result (the kernels are deterministic, so bit for bit).
-        for i in range(len(layer.sets)):
-            layer.step(i)
-        eager_out = [st["out"].clone() for st in layer.sets]
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            for i in range(len(layer.sets)):
-                layer.step(i)                      # warm every buffer set on the capture stream
-            side.synchronize()
-            with torch.cuda.graph(graph, stream=side):
-                for i in range(len(layer.sets)):
-                    layer.step(i)
-        torch.cuda.current_stream().wait_stream(side)
-        reps = max(1, args.steps // len(layer.sets))
-        same = True
-        for rnd in range(3):                       # replays with eager work and synchronisation in between
-            for st in layer.sets:
-                st["out"].zero_()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(reps):
-                graph.replay()
-            torch.cuda.synchronize()
-            t1 = time.perf_counter()
-            same = same and all(torch.equal(st["out"], e) for st, e in zip(layer.sets, eager_out))
-            layer.step(0)
-        g_ms = (t1 - t0) * 1e3 / (reps * len(layer.sets))
-        result["graph"] = {"ms_per_step": g_ms, "tokens_per_s": N / (g_ms * 1e-3), "steps_per_graph": len(layer.sets),
-                           "replays_timed": reps, "matches_eager_bitwise": bool(same)}
+    if not args.no_graph:
+        result["graph"] = graph_replay(layer, args.steps)
     # achievable matrix rate of this box with this kernel: the gate/up GEMM over equal, tile-aligned segments
     M_even = (R // layer.E_local) // 256 * 256
     if M_even > 0 and cfg.dtype == mi.BF16:
@@ -507,11 +519,13 @@ def main():
             also = DEFAULT_ALSO if (args.workload == DEFAULT_WORKLOAD and args.tokens == 0 and args.zipf < 0) else "none"
         names = [n for n in also.split(",") if n and n != "none" and n != args.workload]
         if names:
-            result["also"] = {n: short_run(n, mi.CONFIGS[n], args.steps, args.warmup, args.nbuf) for n in names}
+            result["also"] = {n: short_run(n, mi.CONFIGS[n], args.steps, args.warmup, args.nbuf, not args.no_graph)
+                              for n in names}
     elif args.sweep == "tokens":
         base = mi.CONFIGS["mixtral"]
         result["sweep"] = {"what": "token count on the Mixtral shape (the axis of the paper's Fig. 13)", "points": [
-            dict(tokens=n, **short_run("mixtral", dataclasses.replace(base, N=n), args.steps, args.warmup, args.nbuf))
+            dict(tokens=n, **short_run("mixtral", dataclasses.replace(base, N=n), args.steps, args.warmup, args.nbuf,
+                                       not args.no_graph))
             for n in SWEEP_TOKENS]}
     else:
         base = mi.CONFIGS["mixtral"]

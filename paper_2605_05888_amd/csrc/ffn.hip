@@ -265,9 +265,22 @@ __global__ __launch_bounds__(256) void ffn_f32_down(const float *__restrict__ a,
 template <bool kSwiglu>
 using BigTile = GemmCfg<256, 256, 2, 2, kSwiglu, 64, 5, (MOE_WEIGHTS_AHEAD ? 0x4400 : 0x0044),
                         (MOE_WEIGHTS_AHEAD ? 0x0044 : 0x4400), 0, 64, (MOE_WEIGHTS_AHEAD != 0)>;
-template <bool kSwiglu> using ShallowTile = GemmCfg<64, 256, 1, 4, kSwiglu, 64, 8, 0x1010, 0x2222, 1>;
+#ifndef MOE_SHALLOW_UNITS
+#define MOE_SHALLOW_UNITS 8
+#endif
+template <bool kSwiglu> using ShallowTile = GemmCfg<64, 256, 1, 4, kSwiglu, 64, MOE_SHALLOW_UNITS, 0x1010, 0x2222, 1>;
+
+// The down projection with 128-column tiles, for launches with fewer tiles than compute units (few
+// tokens): every tile of such a launch streams its whole weight panel alone and the launch lasts as
+// long as one tile, so half as wide a panel on twice as many compute units halves it.  Every output
+// element is the same sum in the same order, so y has the same bits as with the 256-column tiles.
+template <bool kSwiglu> using NarrowBig = GemmCfg<256, 128, 2, 2, kSwiglu, 64, 6, 0x2222, 0x1111, 0, 64>;
+template <bool kSwiglu> using NarrowShallow = GemmCfg<64, 128, 1, 4, kSwiglu, 64, 8, 0x1010, 0x1111, 1>;
+// upper bound of the down projection's 256-column tiles up to which the narrow form is used
+constexpr int kNarrowTileBound = 256;
 
 struct FfnPlan {
+    bool narrow2; // the down projection runs with NarrowBig / NarrowShallow
     int BM, out_cols1, out_cols2;
     int n_tiles1, n_tiles2, max_m_tiles;
     size_t off_a, off_hdr1, off_tab1, off_hdr2, off_tab2, off_ready, total;
@@ -280,7 +293,8 @@ static FfnPlan make_plan(int64_t M, int64_t H, int64_t F, int E_local)
     FfnPlan p;
     p.BM = BigTile<true>::BM;
     p.out_cols1 = BigTile<true>::kOutCols; // GEMM1 writes BN/2 columns of `a` per tile
-    p.out_cols2 = BigTile<false>::kOutCols;
+    p.narrow2 = (M / BigTile<false>::BM + E_local) * ceil_div(H, BigTile<false>::kOutCols) <= kNarrowTileBound;
+    p.out_cols2 = p.narrow2 ? NarrowBig<false>::kOutCols : BigTile<false>::kOutCols;
     p.n_tiles1 = (int)ceil_div(F, p.out_cols1);
     p.n_tiles2 = (int)ceil_div(H, p.out_cols2);
     p.max_m_tiles = (int)(M / p.BM) + E_local;
@@ -482,21 +496,21 @@ int launch_ffn_down(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     const FfnWorkspace k = carve(p, ws);
     const uint16_t *wd = static_cast<const uint16_t *>(W_down);
     uint16_t *yb = static_cast<uint16_t *>(y);
-    launch_gemm<BigTile<false>, ShallowTile<false>, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, kPatch, st);
+    if (p.narrow2)
+        launch_gemm<NarrowBig<false>, NarrowShallow<false>, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, kPatch, st);
+    else
+        launch_gemm<BigTile<false>, ShallowTile<false>, false>(k.a, M, (int)F, (int)H, wd, nullptr, yb, k.hdr2, k.tab2, kPatch, st);
     return check_launch("moe_ffn_down");
 }
 
 // Both GEMMs in one launch, the second consuming the first's rows tile by tile (after launch_ffn_schedule).
-int launch_ffn_gate_up_down(const void *xp, int64_t M, int64_t H, int64_t F, int E_local, const void *W_gate,
-                            const void *W_up, const void *W_down, void *y, void *ws, int64_t wait_limit,
-                            hipStream_t st)
+template <class Main2, class Light2>
+static void launch_both(const FfnPlan &p, const FfnWorkspace &k, const void *xp, int64_t M, int64_t H, int64_t F,
+                        const void *W_gate, const void *W_up, const void *W_down, void *y, int64_t wait_limit,
+                        hipStream_t st)
 {
-    const FfnPlan p = make_plan(M, H, F, E_local);
-    const FfnWorkspace k = carve(p, ws);
     using Main1 = BigTile<true>;
     using Light1 = ShallowTile<true>;
-    using Main2 = BigTile<false>;
-    using Light2 = ShallowTile<false>;
     auto kern = grouped_ffn_bf16<Main1, Light1, Main2, Light2>;
     size_t lds_bytes = lds_bytes_of<Main1, Light1>();
     lds_bytes = lds_bytes > lds_bytes_of<Main2, Light2>() ? lds_bytes : lds_bytes_of<Main2, Light2>();
@@ -511,6 +525,18 @@ int launch_ffn_gate_up_down(const void *xp, int64_t M, int64_t H, int64_t F, int
     g1.ready_per_launch = g2.ready_per_launch = Main1::kWaves * p.n_tiles1;
     g1.wait_limit = g2.wait_limit = wait_limit > 0 ? wait_limit : kDefaultWaitLimit;
     hipLaunchKernelGGL(kern, dim3(workgroup_slots(1)), dim3(Main1::kThreads), lds_bytes, st, g1, g2);
+}
+
+int launch_ffn_gate_up_down(const void *xp, int64_t M, int64_t H, int64_t F, int E_local, const void *W_gate,
+                            const void *W_up, const void *W_down, void *y, void *ws, int64_t wait_limit,
+                            hipStream_t st)
+{
+    const FfnPlan p = make_plan(M, H, F, E_local);
+    const FfnWorkspace k = carve(p, ws);
+    if (p.narrow2)
+        launch_both<NarrowBig<false>, NarrowShallow<false>>(p, k, xp, M, H, F, W_gate, W_up, W_down, y, wait_limit, st);
+    else
+        launch_both<BigTile<false>, ShallowTile<false>>(p, k, xp, M, H, F, W_gate, W_up, W_down, y, wait_limit, st);
     return check_launch("moe_ffn_gate_up_down");
 }
 
@@ -571,9 +597,14 @@ int launch_ffn_down_combine(int64_t N, int K, int64_t H, int64_t F, int E_local,
     const int64_t n16 = N * H / 4, n8 = N * H / 8;
     hipLaunchKernelGGL(fill_zero_16B, dim3((unsigned)ceil_div(n16, 256)), dim3(256), 0, st,
                        reinterpret_cast<u32x4 *>(sums), n16);
-    launch_gemm<BigTile<false>, ShallowTile<false>, false, false, true>(
-        k.a, M, (int)F, (int)H, static_cast<const uint16_t *>(W_down), nullptr,
-        reinterpret_cast<uint16_t *>(sums), k.hdr2, k.tab2, kPatch, st, row_of_slot, K, 0u, topk_w);
+    if (p.narrow2)
+        launch_gemm<NarrowBig<false>, NarrowShallow<false>, false, false, true>(
+            k.a, M, (int)F, (int)H, static_cast<const uint16_t *>(W_down), nullptr,
+            reinterpret_cast<uint16_t *>(sums), k.hdr2, k.tab2, kPatch, st, row_of_slot, K, 0u, topk_w);
+    else
+        launch_gemm<BigTile<false>, ShallowTile<false>, false, false, true>(
+            k.a, M, (int)F, (int)H, static_cast<const uint16_t *>(W_down), nullptr,
+            reinterpret_cast<uint16_t *>(sums), k.hdr2, k.tab2, kPatch, st, row_of_slot, K, 0u, topk_w);
     hipLaunchKernelGGL(round_sums_bf16, dim3((unsigned)ceil_div(n8, 256)), dim3(256), 0, st,
                        reinterpret_cast<const f32x4 *>(sums), static_cast<u32x4 *>(out), n8);
     return check_launch("moe_ffn_down_combine");

@@ -299,6 +299,16 @@ def test_grouped_ffn_random_segmentations(G, seed):
     y = G.host(G.gpu_ffn(*args))
     G.check_close(y, oracle.ffn_rows(xp, seg, Wg, Wu, Wd), *G.tolerances(cfg), what="ffn, random segments")
     assert np.array_equal(G.host(G.gpu_ffn(*args)), y)
+    # The down projection picks 128-column tiles when the launch can have only few tiles (judged by an upper
+    # bound from M and the number of experts) and 256-column tiles otherwise; 300 empty experts in front push
+    # this launch over the bound.  Every output element is the same sum in the same order: same bits.
+    pad = 300
+    seg_p = np.concatenate([np.zeros(pad, np.int32), seg]).astype(np.int32)
+    cfg_p = dataclasses.replace(cfg, E=E + pad)
+    Wp = [np.concatenate([mi.host_tensor(cfg_p, s, 0, pad), w]) for s, w in
+          ((mi.STREAM_W_GATE, Wg), (mi.STREAM_W_UP, Wu), (mi.STREAM_W_DOWN, Wd))]
+    y_p = G.host(G.gpu_ffn(args[0], mid.to_device(seg_p), *[mid.to_device(w) for w in Wp]))
+    assert np.array_equal(y_p, y)
 
 
 def test_ffn_remainder_rows_riding_with_the_last_full_tile(G):
