@@ -29,7 +29,11 @@ namespace moe {
 constexpr int kSchedThreads = 256;
 // relative cost of a tile of a one-row-tile expert and of a full tile, for sharing out the workgroup slots
 constexpr int kLightCost = 3, kHeavyCost = 7;
-constexpr int kOrderRows = 4, kOrderCols = 4; // block of the tile order inside an expert
+#ifndef MOE_ORDER_ROWS
+#define MOE_ORDER_ROWS 4
+#define MOE_ORDER_COLS 8
+#endif
+constexpr int kOrderRows = MOE_ORDER_ROWS, kOrderCols = MOE_ORDER_COLS; // block of the tile order inside an expert
 // experts with at most this many rows go through the shallow tile geometry
 constexpr int kLightRows = 64;
 
@@ -160,8 +164,8 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
         const int32_t n_rows_e = clamped_rows(seg_offsets, e, M, lo);
         const int m_tiles = row_tiles(n_rows_e, BM, extra);
         // Inside an expert the tiles go in blocks of kOrderRows x kOrderCols (row tiles x column
-        // tiles): the 16 tiles an XCD takes together then share 4 weight tiles and 4 activation
-        // tiles in its L2, instead of one and 16.
+        // tiles): the 32 tiles an XCD takes together (one per compute unit) then share 8 weight tiles
+        // and 4 activation tiles in its L2, instead of 32 and one.
         const int local = pos - start[c][e];
         const int band_tiles = kOrderRows * n_tiles; // tiles of a full band of kOrderRows row tiles
         int rb = local / band_tiles;
@@ -277,7 +281,10 @@ template <bool kSwiglu> using ShallowTile = GemmCfg<64, 256, 1, 4, kSwiglu, 64, 
 template <bool kSwiglu> using NarrowBig = GemmCfg<256, 128, 2, 2, kSwiglu, 64, 6, 0x2222, 0x1111, 0, 64>;
 template <bool kSwiglu> using NarrowShallow = GemmCfg<64, 128, 1, 4, kSwiglu, 64, 8, 0x1010, 0x1111, 1>;
 // upper bound of the down projection's 256-column tiles up to which the narrow form is used
-constexpr int kNarrowTileBound = 256;
+#ifndef MOE_NARROW_TILE_BOUND
+#define MOE_NARROW_TILE_BOUND 256
+#endif
+constexpr int kNarrowTileBound = MOE_NARROW_TILE_BOUND;
 
 struct FfnPlan {
     bool narrow2; // the down projection runs with NarrowBig / NarrowShallow
@@ -416,7 +423,10 @@ int check_ffn_shape(int dtype, int64_t H, int64_t F)
 }
 
 // consecutive tiles each XCD takes at a time (see stream_position)
-constexpr int kPatch = 16;
+#ifndef MOE_PATCH
+#define MOE_PATCH 32
+#endif
+constexpr int kPatch = MOE_PATCH;
 // polls (about a microsecond each) a dependent tile spends on its rows before it gives up: seconds
 constexpr int64_t kDefaultWaitLimit = (int64_t)1 << 22;
 

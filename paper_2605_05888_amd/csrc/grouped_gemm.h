@@ -30,7 +30,7 @@
 //     silu(g)*u, so g and u never reach memory.
 //
 // Scheduling: the grid is persistent, one workgroup per compute unit.  Workgroups draw tiles
-// from per-XCD counters of the tile table (own XCD first), so the 16 tiles an XCD holds at a
+// from per-XCD counters of the tile table (own XCD first), so the tiles an XCD holds at a
 // time are neighbours in the table's order; while a workgroup multiplies the last K tiles of
 // one output tile, its loads already fetch the first K tiles of its next one.  The table has
 // two streams of tiles, served by two tile geometries inside the one kernel: 256x256 tiles, and
@@ -86,6 +86,9 @@ constexpr int kReadyBit = 1 << 30;                 // in a drawn tile word: the 
 // and a device-scope release, i.e. a write-back of the whole L2, per wavefront and tile (measured: tens
 // of microseconds each, the launch takes twice as long); 2 = ordinary stores and no write-back: NOT
 // coherent, for timing experiments only.
+#ifndef MOE_LIGHT_AUX
+#define MOE_LIGHT_AUX 2 // cache policy of a shallow tile's weight loads: 2 = non-temporal
+#endif
 #ifndef MOE_DEP_STORE_THROUGH
 #define MOE_DEP_STORE_THROUGH 1
 #endif
@@ -596,7 +599,7 @@ __device__ __forceinline__ void gemm_phase(const GemmArgs &g)
         // hint (aux bit 1) they do not push the other tiles' shared operands out of the caches.
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             rs, (lds_ptr)(lds + Cfg::unit_base(unit) + (wave * Cfg::kBGroups + g) * 1024), 16, b_off[g],
-            (here ? t : t - KT) * (kBK * 2), 0, Cfg::kKind == 1 ? 2 : 0);
+            (here ? t : t - KT) * (kBK * 2), 0, Cfg::kKind == 1 ? MOE_LIGHT_AUX : 0);
     };
 
     // ---- the ring.  K tile t keeps the rows of its "far" operand (the one whose loads run ahead in
