@@ -57,9 +57,16 @@ __global__ __launch_bounds__(kWave *kWavesPerBlock) void layout_unit_hist(
     for (int e = lane; e < E; e += kWave)
         cnt[e] = 0;
     const int64_t r0 = (int64_t)u * kUnitRows;
+    // the unit's rows are fetched up front: one memory round trip per unit instead of one per step
+    int ev[kUnitSteps];
+#pragma unroll
     for (int s = 0; s < kUnitSteps; ++s) {
-        int64_t r = r0 + s * kWave + lane;
-        int e = (r < R) ? idx[r] : -1;
+        const int64_t r = r0 + s * kWave + lane;
+        ev[s] = (r < R) ? idx[r] : -1;
+    }
+#pragma unroll
+    for (int s = 0; s < kUnitSteps; ++s) {
+        const int e = ev[s];
         bool valid = (e >= 0) && (e < E);
         uint64_t m = same_expert_lanes(e, valid, nbits);
         if (valid && (m & lanes_below(lane)) == 0) // lowest lane of its group
@@ -152,6 +159,15 @@ __global__ __launch_bounds__(kWave *kWavesPerBlock) void layout_assign_slots(
     if (u >= U && !writer)
         return;
 
+    // the unit's rows are fetched before the cursors are set up: their round trip runs under that
+    const int64_t r0 = (int64_t)u * kUnitRows;
+    int ev[kUnitSteps];
+#pragma unroll
+    for (int s = 0; s < kUnitSteps; ++s) {
+        const int64_t r = r0 + s * kWave + lane;
+        ev[s] = (r < R) ? idx[r] : -1;
+    }
+
     region_offsets(expert_counts, E, lane, cursor);
 
     if (writer)
@@ -162,10 +178,10 @@ __global__ __launch_bounds__(kWave *kWavesPerBlock) void layout_assign_slots(
     for (int e = lane; e < E; e += kWave)
         cursor[e] += unit_base[(int64_t)e * U + u];
 
-    const int64_t r0 = (int64_t)u * kUnitRows;
+#pragma unroll
     for (int s = 0; s < kUnitSteps; ++s) {
-        int64_t r = r0 + s * kWave + lane;
-        int e = (r < R) ? idx[r] : -1;
+        const int64_t r = r0 + s * kWave + lane;
+        const int e = ev[s];
         bool valid = (e >= 0) && (e < E);
         uint64_t m = same_expert_lanes(e, valid, nbits);
         uint64_t below = m & lanes_below(lane);
