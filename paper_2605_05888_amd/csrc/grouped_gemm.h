@@ -1045,11 +1045,13 @@ __device__ __forceinline__ void gemm_phase(const GemmArgs &g)
 
     // ---- the workgroup's first three tiles.  The words still hold what an earlier launch left
     //      there, so these stores have to be in memory before anyone looks.
-    //      A consumer phase with only a few tiles per workgroup draws one tile at a time instead:
-    //      its workgroups arrive one by one as they run out of producer tiles, and the early ones
-    //      would take three tiles each where two are everybody's share.  Such a tile starts cold
-    //      (no operands fetched behind its predecessor), which long or few tiles can afford.
-    const bool one_at_a_time = kDep == 2 && len0 + len1 < 4 * (int)gridDim.x;
+    //      A launch with about one tile per workgroup draws one tile at a time instead: the first
+    //      workgroups to start would otherwise take three tiles each and leave others without.  So
+    //      does a consumer phase with only a few tiles per workgroup, whose workgroups arrive one
+    //      by one as they run out of producer tiles.  Such a tile starts cold (no operands fetched
+    //      behind its predecessor), which long or few tiles can afford.
+    const int n_tiles_all = len0 + len1, n_groups = (int)gridDim.x;
+    const bool one_at_a_time = n_tiles_all < n_groups + n_groups / 2 || (kDep == 2 && n_tiles_all < 4 * n_groups);
     bool again;
     do {
         seq = 1;
