@@ -237,8 +237,11 @@ int moe_ffn_gate_up(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
  * before any down-projection tile is drawn, so a wait always ends; the limit turns a
  * broken schedule into an exit instead of a hang: the workgroup leaves, sets the
  * workspace's error word (moe_ffn_status then returns MOE_ERR_STATE) and y stays
- * incomplete.  The call itself still returns MOE_OK.  MOE_F32: runs the two simple
- * kernels one after the other.
+ * incomplete.  The call itself still returns MOE_OK.  MOE_BF16 needs a 128-byte aligned
+ * ws (with F % 64 == 0, as for every bf16 FFN, each row of the activation then is a whole
+ * number of cache lines, so no line holds rows of two row tiles, one complete and one
+ * still being written); otherwise MOE_ERR_UNSUPPORTED, and the two separate calls serve.  MOE_F32: runs the two
+ * simple kernels one after the other.
  */
 int moe_ffn_gate_up_down(const void *xp, int dtype, int64_t M, int64_t H, int64_t F,
                          int E_local, const int32_t *seg_offsets,

@@ -399,8 +399,17 @@ extern "C" int moe_ffn_gate_up_down(const void *xp, int dtype, int64_t M, int64_
     MOE_NEED(W_down);
     MOE_NEED(y);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (dtype == MOE_BF16)
+    if (dtype == MOE_BF16) {
+        // A down-projection tile reads rows of `a` while other rows are still being written by other
+        // XCDs.  A cache line that held rows of two row tiles could be fetched for the first and found,
+        // stale, for the second; rows that are whole lines (F % 64 == 0 holds for every bf16 FFN, and
+        // `a` starts the workspace) rule that out.
+        if (reinterpret_cast<uintptr_t>(ws) % 128 != 0)
+            return fail(MOE_ERR_UNSUPPORTED,
+                        "moe_ffn_gate_up_down needs a 128-byte aligned ws (rows of the activation must be whole "
+                        "cache lines); use moe_ffn_gate_up + moe_ffn_down");
         return launch_ffn_gate_up_down(xp, M, H, F, E_local, W_gate, W_up, W_down, y, ws, wait_limit, st);
+    }
     // fp32 (correctness path): the two simple kernels, one after the other
     MOE_TRY(launch_ffn_gate_up(xp, dtype, M, H, F, E_local, seg_offsets, W_gate, W_up, ws, st));
     return launch_ffn_down(dtype, M, H, F, E_local, seg_offsets, W_down, y, ws, st);

@@ -480,6 +480,30 @@ def test_one_launch_ffn_gives_up_at_its_poll_limit_and_says_so(G):
     assert torch.equal(y2, y3) and bool(y2.any())
 
 
+def test_one_launch_ffn_refuses_activation_rows_that_share_cache_lines(G):
+    """Rows of the activation that are not whole 128-byte lines (a workspace that is not 128-byte aligned)
+    could leave a stale line in an XCD's L2: refused before any launch."""
+    import moe_inputs.device as mid
+    import torch
+    import paper_2605_05888_amd as hub
+    M, H, E = 300, 128, 2
+    dseg = mid.to_device(np.array([0, 100, M], np.int32))
+    for F, shift in ((192, 16), (192, 64)):
+        _say("ffn in one launch, refused", (F, shift))
+        buf = torch.zeros(hub.workspace_bytes(hub.OP_GROUPED_FFN, N=M, H=H, E=E, F=F) + 256, dtype=torch.uint8, device="cuda:0")
+        ws = buf[shift:shift + buf.numel() - 256]
+        xp = torch.zeros((M, H), dtype=torch.bfloat16, device="cuda:0")
+        Wg = torch.zeros((E, F, H), dtype=torch.bfloat16, device="cuda:0")
+        Wd = torch.zeros((E, H, F), dtype=torch.bfloat16, device="cuda:0")
+        y = torch.ones((M, H), dtype=torch.bfloat16, device="cuda:0")
+        hub.moe_ffn_schedule(hub.BF16, M, H, F, dseg, ws)
+        with pytest.raises(hub.MoEHubError) as err:
+            hub.moe_ffn_gate_up_down(xp, dseg, Wg, Wg, Wd, y, ws)
+        assert err.value.code == -2 and "128-byte" in str(err.value)
+        torch.cuda.synchronize()
+        assert bool((y == 1).all())
+
+
 @pytest.mark.parametrize("name", list(SMALL))
 def test_gate_up_with_fused_gather_equals_permute_then_gate_up(G, name):
     """GEMM1 fetching its rows through row_of_slot from x gives the bits of permute + GEMM1; the whole
