@@ -63,6 +63,9 @@ def parse_args():
                     help="override the Zipf exponent of expert popularity (0 = uniform)")
     ap.add_argument("--no-graph", action="store_true",
                     help="skip the HIP-graph replay of the step (one graph of all buffer sets' steps)")
+    ap.add_argument("--ffn-split", action="store_true",
+                    help="also time the two GEMMs over only the experts with more than 64 rows, and over only the "
+                         "others (key 'ffn.split_by_expert_size')")
     ap.add_argument("--nbuf", type=int, default=0, help="activation buffer sets rotated per step (0 = auto)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target time of the oracle sample (0 = skip)")
     return ap.parse_args()
@@ -315,6 +318,46 @@ def graph_replay(layer, steps):
             "replays_timed": reps, "matches_eager_bitwise": bool(same)}
 
 
+def ffn_split(layer, cfg, light_rows=64, reps=20):
+    """GEMM times (HIP events, mean of `reps` launches after 3 untimed ones) with the realised expert counts, with
+    only the experts above `light_rows` rows, and with only the others; rows and weights are the layer's own."""
+    import numpy as np
+    import torch
+    hub = layer.hub
+    s0 = layer.sets[0]
+    counts = s0["cnt"].cpu().numpy().astype(np.int64)
+    H, F = cfg.H, cfg.F
+    out = {"light_rows_max": light_rows}
+    for tag, c in (("all", counts), ("heavy_only", np.where(counts > light_rows, counts, 0)),
+                   ("light_only", np.where(counts <= light_rows, counts, 0))):
+        M = int(c.sum())
+        if M == 0:
+            continue
+        seg = torch.tensor(np.concatenate([[0], np.cumsum(c)]).astype(np.int32), device="cuda:0")
+        hub.moe_ffn_schedule(layer.code, M, H, F, seg, s0["ffn_ws"])
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        for timed in (False, True):
+            n = reps if timed else 3
+            if timed:
+                ev[0].record()
+            for _ in range(n):
+                hub.moe_ffn_gate_up(s0["xp"][:M], seg, layer.W_gate, layer.W_up, s0["ffn_ws"])
+            if timed:
+                ev[1].record()
+            for _ in range(n):
+                hub.moe_ffn_down(seg, layer.W_down, s0["y"][:M], s0["ffn_ws"])
+        ev[2].record()
+        torch.cuda.synchronize()
+        t1, t2 = ev[0].elapsed_time(ev[1]) * 1e3 / reps, ev[1].elapsed_time(ev[2]) * 1e3 / reps
+        n_exp = int((c > 0).sum())
+        out[tag] = {"rows": M, "experts": n_exp, "gate_up_us": t1, "down_us": t2,
+                    "gate_up_tflops": 4.0 * M * H * F / t1 / 1e6, "down_tflops": 2.0 * M * H * F / t2 / 1e6,
+                    "gate_up_weight_GBs": n_exp * 2.0 * F * H * 2 / t1 / 1e3, "down_weight_GBs": n_exp * F * H * 2.0 / t2 / 1e3}
+    # leave the layer's own schedule behind
+    hub.moe_ffn_schedule(layer.code, layer.R, H, F, s0["off"], s0["ffn_ws"])
+    return out
+
+
 def pick_nbuf(cfg, nbuf_arg):
     N, H, K, F, b = cfg.N, cfg.H, cfg.K, cfg.F, cfg.elt_bytes
     act_bytes = (2 * N * H + 2 * N * K * H + N * K * F) * b
@@ -494,6 +537,10 @@ def main():
         g1.record()
         torch.cuda.synchronize()
         result["ffn"]["tflops_gate_up_equal_segments"] = reps * 4.0 * rows * H * F / (g0.elapsed_time(g1) * 1e-3) / 1e12
+    # Which experts cost what: the two GEMMs over all experts, over those with more than 64 rows only (tiles that
+    # are bound by the matrix cores) and over the others only (tiles that stream their weights once for a few rows).
+    if args.ffn_split and cfg.dtype == mi.BF16 and not layer.ep:
+        result["ffn"]["split_by_expert_size"] = ffn_split(layer, cfg)
     # achievable copy bandwidth of this machine: plain 1 GiB device-to-device copy (read + write bytes)
     import moe_inputs.device as mid
     src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")

@@ -145,6 +145,10 @@ constexpr int kRtK = 128;        // K tile
 #define MOE_RT_WAVES 4
 #endif
 constexpr int kRtWaves = MOE_RT_WAVES;
+#ifndef MOE_RT_K
+#define MOE_RT_K 128
+#endif
+constexpr int kRtKm = MOE_RT_K;  // K tile of the matrix-core form
 #ifndef MOE_RT_STAGES
 #define MOE_RT_STAGES 2
 #endif
@@ -339,13 +343,13 @@ __global__ __launch_bounds__(kWave *kRtWaves, 2) void router_logits_mfma(
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int kXb = kBf16 ? 2 : 4;                  // bytes per x element
-    constexpr int kXRow = kRtK * kXb;                   // bytes of one token row in a tile
+    constexpr int kXRow = kRtKm * kXb;                   // bytes of one token row in a tile
     constexpr int kXTile = kRtTok * kXRow;              // per wavefront
-    constexpr int kWTile = kRtK * kRtExp * 4;           // 8 KiB
+    constexpr int kWTile = kRtKm * kRtExp * 4;           // 8 KiB
     constexpr int kStage = kWTile + kRtWaves * kXTile;
     constexpr int kXLoads = kXTile / 1024;              // per wavefront per tile
     constexpr int kWLoads = kWTile / 1024 / kRtWaves;   // per wavefront per tile
-    static_assert(kRtTok == 8 && kRtExp == 16 && kRtK == 128, "the index arithmetic below");
+    static_assert(kRtTok == 8 && kRtExp == 16 && kRtKm % 64 == 0, "the index arithmetic below");
     constexpr int kStages = MOE_RT_STAGES;               // LDS ring: the loads run kStages - 1 tiles ahead
     __shared__ __attribute__((aligned(1024))) unsigned char lds[kStages * kStage];
     const int lane = threadIdx.x % kWave;
@@ -369,13 +373,15 @@ __global__ __launch_bounds__(kWave *kRtWaves, 2) void router_logits_mfma(
 #pragma unroll
     for (int gl = 0; gl < kXLoads; ++gl) {
         const int t = gl * (kWave / kLanesPerRow) + lane / kLanesPerRow;
-        x_off[gl] = (t * H + (lane % kLanesPerRow) * (16 / kXb)) * kXb;
+        // 16-byte chunk j of token row t sits at chunk slot j ^ 4 (t % 4): the four rows a read below
+        // touches then fall into different quarters of the banks
+        x_off[gl] = (t * H + ((lane % kLanesPerRow) ^ ((t & 3) * 4)) * (16 / kXb)) * kXb;
     }
     // (the K tile's position goes into the resources, see router_logits_tiled)
     auto clamp32 = [](int64_t b) { return (unsigned)(b < 0 ? 0 : (b > 0xFFFFFFFFll ? 0xFFFFFFFFll : b)); };
     auto issue = [&](int kt) {
         unsigned char *st = lds + (kt % kStages) * kStage;
-        const int k0 = kt * kRtK;
+        const int k0 = kt * kRtKm;
         const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<float *>(W_r + (int64_t)k0 * E + e0), 0, clamp32(k0 < H ? ((int64_t)(H - k0) * E - e0) * 4 : 0),
             0x00020000);
@@ -400,7 +406,7 @@ __global__ __launch_bounds__(kWave *kRtWaves, 2) void router_logits_mfma(
     for (int i = 0; i < 32; ++i)
         acc[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-    const int KT = (H + kRtK - 1) / kRtK;
+    const int KT = (H + kRtKm - 1) / kRtKm;
     // (tiles past the last one are issued too: their resources hold no bytes, so they fetch nothing and
     // the number of loads in flight stays what the wait below counts on)
 #pragma unroll
@@ -417,7 +423,7 @@ __global__ __launch_bounds__(kWave *kRtWaves, 2) void router_logits_mfma(
         const unsigned char *st = lds + (kt % kStages) * kStage;
         const unsigned char *xs = st + kWTile + wave * kXTile;
 #pragma unroll
-        for (int sub = 0; sub < kRtK / kWave; ++sub) {
+        for (int sub = 0; sub < kRtKm / kWave; ++sub) {
             // b operands: for every g the four q of this lane's expert chunk
             f32x4 wv[4];
 #pragma unroll
@@ -427,7 +433,7 @@ __global__ __launch_bounds__(kWave *kRtWaves, 2) void router_logits_mfma(
             float xv[2][4];
 #pragma unroll
             for (int p = 0; p < 2; ++p) {
-                const unsigned char *px = xs + (4 * p + c) * kXRow + (64 * sub + 4 * blk) * kXb;
+                const unsigned char *px = xs + (4 * p + c) * kXRow + (((64 * sub + 4 * blk) * kXb) ^ (c * 64));
                 if (kBf16) {
                     const u32x2 raw = *reinterpret_cast<const u32x2 *>(px);
                     xv[p][0] = __uint_as_float(raw[0] << 16);
