@@ -941,7 +941,7 @@ __device__ __forceinline__ void gemm_phase(const GemmArgs &g)
                 // others through LDS.  Every producer tile has been drawn by a workgroup that waits for
                 // nothing, so the wait ends; the poll limit only guards against a broken schedule.
                 if (!(cur_t & kReadyBit)) {
-                    volatile int32_t *const verdict = reinterpret_cast<volatile int32_t *>(lds);
+                    volatile int32_t *const outcome = reinterpret_cast<volatile int32_t *>(lds);
                     if (tid == 0) {
                         int64_t polls = 0;
                         bool ok = rows_complete(cur.m0);
@@ -951,10 +951,10 @@ __device__ __forceinline__ void gemm_phase(const GemmArgs &g)
                         }
                         if (!ok)
                             __hip_atomic_store(&hdr->error, kDependencyTimeout, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        *verdict = ok ? 1 : 0;
+                        *outcome = ok ? 1 : 0;
                     }
                     __syncthreads();
-                    const bool ok = __builtin_amdgcn_readfirstlane(*verdict) != 0;
+                    const bool ok = __builtin_amdgcn_readfirstlane(*outcome) != 0;
                     __syncthreads();
                     if (!ok) { // give up: this workgroup's tiles stay undone, the error word says so
                         cur_t = nxt_t = -1;
