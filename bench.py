@@ -66,6 +66,9 @@ def parse_args():
     ap.add_argument("--ffn-split", action="store_true",
                     help="also time the two GEMMs over only the experts with more than 64 rows, and over only the "
                          "others (key 'ffn.split_by_expert_size')")
+    ap.add_argument("--stream-probe", action="store_true",
+                    help="also measure how fast 8 ... 256 workgroups, one per compute unit, stream a 4 GiB buffer from "
+                         "memory into LDS (key 'stream_probe'): the per-compute-unit ceiling of weight streaming")
     ap.add_argument("--nbuf", type=int, default=0, help="activation buffer sets rotated per step (0 = auto)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target time of the oracle sample (0 = skip)")
     return ap.parse_args()
@@ -554,6 +557,23 @@ def main():
     torch.cuda.synchronize()
     result["dispatch_combine"]["plain_copy_GBs"] = 5 * 2 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del src, dst
+    if args.stream_probe:
+        buf = torch.empty(4 << 30, dtype=torch.uint8, device="cuda:0")
+        buf.fill_(1)
+        pts = []
+        for wgs in (8, 32, 64, 128, 256):
+            best = None
+            for _ in range(3):
+                c0.record()
+                nbytes = mid.stream_read(buf, wgs, row_bytes=2 * cfg.H)
+                c1.record()
+                torch.cuda.synchronize()
+                t = c0.elapsed_time(c1) * 1e-3
+                best = t if best is None or t < best else best
+            pts.append({"workgroups": wgs, "GBs": nbytes / best / 1e9, "GBs_per_workgroup": nbytes / best / 1e9 / wgs})
+        result["stream_probe"] = {"what": "buffer loads into LDS, rows of 2*H bytes, 32 KB in flight per workgroup, no reuse",
+                                  "points": pts}
+        del buf
     if args.cpu_seconds > 0:
         result["cpu_baseline"] = cpu_baseline(cfg, layer, args.cpu_seconds)
     del layer, st0

@@ -50,6 +50,24 @@ def copy_bytes(dst, src):
         raise RuntimeError("copy kernel launch failed")
 
 
+def stream_read(src, workgroups: int, row_bytes: int = 5760, panels: int = 64):
+    """Read yardstick: `workgroups` workgroups each stream their own slice of the byte tensor `src` into LDS (rows
+    of row_bytes, 16-byte buffer loads, 32 KB in flight per workgroup).  Returns the bytes read in total."""
+    import torch
+    assert src.is_cuda and src.is_contiguous() and src.dtype == torch.uint8
+    region = (src.numel() // workgroups) & ~4095
+    panels = min(panels, region // (4 * 32 * row_bytes))
+    lib = _load()
+    lib.moe_inputs_stream_read.restype = ctypes.c_int64
+    lib.moe_inputs_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                           ctypes.c_void_p]
+    per = lib.moe_inputs_stream_read(src.data_ptr(), region, row_bytes, panels, workgroups,
+                                     torch.cuda.current_stream().cuda_stream)
+    if per <= 0:
+        raise RuntimeError("stream_read: bad arguments or launch failure")
+    return per * workgroups
+
+
 def fill_normal(out, seed: int, stream: int, start: int, sigma: float):
     """Fills the contiguous device tensor `out` (bf16 or fp32) with flat elements
     [start, start + out.numel()) of the stream."""

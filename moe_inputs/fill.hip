@@ -54,7 +54,48 @@ __global__ void copy_16B(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
         dst[i] = src[i];
 }
 
+// Read yardstick: each workgroup (4 wavefronts) streams its own region of `region` bytes from memory into LDS
+// with 16-byte buffer loads, 32 of them in flight per wavefront, rows of `row_bytes` (a multiple of 128) taken
+// 128 rows x 128 bytes at a time: the access pattern of a weight panel.  Nothing is computed.
+constexpr int kStreamWaves = 4, kStreamDepth = 8;
+__global__ __launch_bounds__(kStreamWaves * 64) void stream_read(const unsigned char *__restrict__ src, uint64_t region,
+                                                                int row_bytes, int panels, unsigned *__restrict__ out)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[kStreamWaves * 4096];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const unsigned char *p = src + (uint64_t)blockIdx.x * region + (uint64_t)(wave * 32 + lane / 8) * row_bytes + (lane % 8) * 16;
+    for (int pn = 0; pn < panels; ++pn) {
+        for (int koff = 0; koff < row_bytes; koff += 128) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(p + (uint64_t)j * 8 * row_bytes + koff),
+                                                 (__attribute__((address_space(3))) void *)(lds + (wave * 4 + j) * 1024), 16, 0, 0);
+            __builtin_amdgcn_s_waitcnt(0x0F70 | (((kStreamDepth - 1) * 4) & 15) | ((((kStreamDepth - 1) * 4) >> 4) << 14)); // vmcnt
+        }
+        p += (uint64_t)kStreamWaves * 32 * row_bytes;
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
+    __syncthreads();
+    if (out)
+        out[blockIdx.x * kStreamWaves * 64 + tid] = lds[tid];
+}
+
 }  // namespace
+
+// Launches `workgroups` workgroups that each read `panels` panels of 128 rows x row_bytes from their own region of
+// `region` bytes of src (device pointer, at least workgroups * region bytes).  Returns the bytes one workgroup reads
+// (0: bad arguments, -1: launch failed).
+extern "C" int64_t moe_inputs_stream_read(const void *src, uint64_t region, int row_bytes, int panels, int workgroups,
+                                          void *stream)
+{
+    const uint64_t panel = (uint64_t)kStreamWaves * 32 * row_bytes;
+    if (!src || row_bytes <= 0 || row_bytes % 128 != 0 || panels <= 0 || workgroups <= 0 || panel * panels > region)
+        return 0;
+    hipLaunchKernelGGL(stream_read, dim3(workgroups), dim3(kStreamWaves * 64), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const unsigned char *>(src), region, row_bytes, panels, (unsigned *)nullptr);
+    return hipGetLastError() == hipSuccess ? (int64_t)(panel * panels) : -1;
+}
 
 // Copies `bytes` (a multiple of 16) from src to dst, both device pointers.
 extern "C" int moe_inputs_copy(void *dst, const void *src, uint64_t bytes, void *stream)
