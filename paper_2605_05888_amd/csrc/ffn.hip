@@ -61,7 +61,7 @@ __device__ __forceinline__ int32_t clamped_rows(const int32_t *seg_offsets, int 
 
 // One launch builds the tables of both GEMMs: blockIdx.y picks the set of arguments.
 struct TableArgs {
-    int n_tiles, max_tiles;
+    int n_tiles, max_tiles, out_cols;
     TileTableHeader *hdr;
     TileEntry *table;
 };
@@ -143,6 +143,7 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
         hdr->all_done = 0;
         hdr->magic = kTableMagic;
         hdr->rows = (int32_t)M;
+        hdr->out_cols = args.out_cols;
         for (int s = 0; s < 2; ++s)
             for (int x = 0; x < kXcds; ++x)
                 hdr->next[s][x] = 0;
@@ -464,7 +465,8 @@ int launch_ffn_schedule(int dtype, int64_t M, int64_t H, int64_t F, int E_local,
     const int max_both = k.max1 > k.max2 ? k.max1 : k.max2;
     hipLaunchKernelGGL(build_tile_table, dim3((unsigned)ceil_div(max_both, kSchedThreads), 2),
                        dim3(kSchedThreads), 0, st, seg_offsets, E_local, M, p.BM, BigTile<true>::kExtra, kLightRows,
-                       TableArgs{p.n_tiles1, k.max1, k.hdr1, k.tab1}, TableArgs{p.n_tiles2, k.max2, k.hdr2, k.tab2},
+                       TableArgs{p.n_tiles1, k.max1, p.out_cols1, k.hdr1, k.tab1},
+                       TableArgs{p.n_tiles2, k.max2, p.out_cols2, k.hdr2, k.tab2},
                        k.ready);
     return check_launch("moe_ffn_schedule");
 }

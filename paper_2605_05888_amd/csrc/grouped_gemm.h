@@ -68,7 +68,7 @@ struct TileTableHeader {
     int32_t magic;          // kTableMagic once build_tile_table has filled the table ...
     int32_t rows;           // ... for this many rows
     int32_t error;          // kNoScheduleError / kDependencyTimeout, see below (cleared by the schedule)
-    int32_t pad;
+    int32_t out_cols;       // output columns per tile the table was built for (a kernel of another geometry must not walk it)
     int32_t next[2][kXcds]; // per stream and XCD: tickets handed out so far
     // dependency-driven launches (both GEMMs in one kernel), kept in GEMM1's header:
     int32_t epoch;          // such launches completed over this schedule
@@ -317,7 +317,7 @@ __device__ __forceinline__ void gemm_phase(const GemmArgs &g)
     //      (LDS is full and a register cannot cross wavefronts): {tile, sequence number}, stored
     //      and loaded as one 8-byte unit.  A reader that finds an older sequence number reads
     //      again, so nobody waits for the store to land and nobody acts on a stale tile.
-    if (hdr->magic != kTableMagic || hdr->rows != (int32_t)M) {
+    if (hdr->magic != kTableMagic || hdr->rows != (int32_t)M || hdr->out_cols != Main::kOutCols) {
         // no schedule for these rows in this workspace: nothing to go by.  The host is not waiting for
         // this kernel, so all it can do is leave a word that moe_ffn_status finds.
         if (blockIdx.x == 0 && threadIdx.x == 0)
@@ -684,6 +684,7 @@ __device__ __forceinline__ void gemm_phase(const GemmArgs &g)
         MOE_WAIT_VMCNT(kXWait);
         const u32x4 &x = xa[ks < kXRegs ? ks : 0];
         if constexpr (kHalf) {
+            static_assert(!kSwiglu || Cfg::kBlkN % 4 == 0, "a gate block and its up block per wavefront row");
             // one extra block row for the whole workgroup: wavefront row wm takes column blocks
             // wm, wm + 2, ... of its wavefront column (for SwiGLU a gate block and its up block)
 #pragma unroll
