@@ -33,6 +33,9 @@ constexpr int kLightCost = 3, kHeavyCost = 7;
 #define MOE_ORDER_ROWS 4
 #define MOE_ORDER_COLS 8
 #endif
+#ifndef MOE_ORDER_LONG_FIRST
+#define MOE_ORDER_LONG_FIRST 1
+#endif
 constexpr int kOrderRows = MOE_ORDER_ROWS, kOrderCols = MOE_ORDER_COLS; // block of the tile order inside an expert
 // experts with at most this many rows go through the shallow tile geometry
 constexpr int kLightRows = 64;
@@ -178,10 +181,29 @@ __global__ __launch_bounds__(kSchedThreads) void build_tile_table(
         const int in_block = in_band - cb * kOrderCols * h;
         TileEntry t;
         t.expert = e;
-        const int row_tile = rb * kOrderRows + in_block % h;
+        int row_in_band = in_block % h, col_in_block = in_block / h;
+#if MOE_ORDER_LONG_FIRST
+        // The expert's last row tile takes another time than the full ones: longer when a remainder rides
+        // with it, shorter when it is ragged.  Inside a block the long tiles are handed out first and the
+        // short ones last, so that the workgroups that finish their previous tile early take the long ones
+        // (it is the same set of tiles per block either way).
+        if (rb == last_band && h > 1 && n_rows_e != m_tiles * BM) {
+            const int wb = n_tiles - cb * kOrderCols < kOrderCols ? n_tiles - cb * kOrderCols : kOrderCols;
+            const bool tall = n_rows_e > m_tiles * BM;
+            const int first = tall ? wb : 0;                  // tiles of the odd row handed out before the others
+            if (tall && in_block < wb) {
+                row_in_band = h - 1, col_in_block = in_block;
+            } else if (!tall && in_block >= wb * (h - 1)) {
+                row_in_band = h - 1, col_in_block = in_block - wb * (h - 1);
+            } else {
+                row_in_band = (in_block - first) % (h - 1), col_in_block = (in_block - first) / (h - 1);
+            }
+        }
+#endif
+        const int row_tile = rb * kOrderRows + row_in_band;
         // rows that the expert's last tile computes beyond its BM
         const int ext = row_tile == m_tiles - 1 && n_rows_e > m_tiles * BM ? n_rows_e - m_tiles * BM : 0;
-        t.n_tile = (cb * kOrderCols + in_block / h) | (ext << kTileColBits);
+        t.n_tile = (cb * kOrderCols + col_in_block) | (ext << kTileColBits);
         t.m0 = (int32_t)lo + row_tile * BM;
         t.m_end = (int32_t)lo + n_rows_e;
         table[L] = t;
