@@ -1052,7 +1052,16 @@ __device__ __forceinline__ void gemm_phase(const GemmArgs &g)
     //      by one as they run out of producer tiles.  Such a tile starts cold (no operands fetched
     //      behind its predecessor), which long or few tiles can afford.
     const int n_tiles_all = len0 + len1, n_groups = (int)gridDim.x;
-    const bool one_at_a_time = n_tiles_all < n_groups + n_groups / 2 || (kDep == 2 && n_tiles_all < 4 * n_groups);
+    // Drawing ahead also means that the last tiles of a launch are held by workgroups that are still busy
+    // while others have run out: with only a few tiles per workgroup, and tiles long enough that a cold
+    // start is a small part of them, one at a time is the better deal as well (512 tiles of 224 K tiles on
+    // 256 workgroups: some took three and some one).
+#ifndef MOE_LEAN_ROUNDS
+#define MOE_LEAN_ROUNDS 8  // fewer tiles than this per workgroup ...
+#define MOE_LEAN_KTILES 64 // ... each at least this many K tiles long (a cold start costs about five)
+#endif
+    const bool one_at_a_time = n_tiles_all < n_groups + n_groups / 2 || (kDep == 2 && n_tiles_all < 4 * n_groups) ||
+                               (n_tiles_all < MOE_LEAN_ROUNDS * n_groups && KT >= MOE_LEAN_KTILES);
     bool again;
     do {
         seq = 1;
