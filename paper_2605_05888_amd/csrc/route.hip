@@ -145,10 +145,10 @@ constexpr int kRtK = 128;        // K tile
 #define MOE_RT_WAVES 4
 #endif
 constexpr int kRtWaves = MOE_RT_WAVES;
-#ifndef MOE_RT_K
-#define MOE_RT_K 128
-#endif
-constexpr int kRtKm = MOE_RT_K;  // K tile of the matrix-core form
+// K tile of the matrix-core form: 128; 256 where a launch has one or two expert tiles only (E <= 32): few
+// workgroups, each with a long reduction, and half as many barriers pay there (E = 8: -11 %), while with
+// many expert tiles the larger LDS footprint costs more than that (E = 256: +7 %).
+constexpr int kRtKShort = 128, kRtKLong = 256;
 #ifndef MOE_RT_STAGES
 #define MOE_RT_STAGES 2
 #endif
@@ -336,7 +336,7 @@ __device__ __forceinline__ void fold_lanes(float *v, bool upper)
     }
 }
 
-template <bool kBf16>
+template <bool kBf16, int kRtKm>
 __global__ __launch_bounds__(kWave *kRtWaves, 2) void router_logits_mfma(
     const void *__restrict__ x, int64_t N, int H, const float *__restrict__ W_r,
     const float *__restrict__ bias, int E, float *__restrict__ logits)
@@ -577,12 +577,15 @@ int launch_route(const void *x, int dtype, int64_t N, int64_t H, const float *W_
     if (E % 4 == 0 && H * (int64_t)E * 4 < ((int64_t)1 << 31) && H * 8 * 4 < ((int64_t)1 << 31)) {
         const dim3 grid((unsigned)ceil_div(E, kRtExp), (unsigned)ceil_div(N, (int64_t)kRtTok * kRtWaves));
 #if MOE_ROUTER_MFMA
-        if (dtype == MOE_BF16)
-            hipLaunchKernelGGL(router_logits_mfma<true>, grid, dim3(kWave * kRtWaves), 0, st, x, N, (int)H, W_r,
-                               bias, E, logits);
+        if (dtype == MOE_BF16 && E <= 2 * kRtExp)
+            hipLaunchKernelGGL((router_logits_mfma<true, kRtKLong>), grid, dim3(kWave * kRtWaves), 0, st, x, N, (int)H,
+                               W_r, bias, E, logits);
+        else if (dtype == MOE_BF16)
+            hipLaunchKernelGGL((router_logits_mfma<true, kRtKShort>), grid, dim3(kWave * kRtWaves), 0, st, x, N, (int)H,
+                               W_r, bias, E, logits);
         else
-            hipLaunchKernelGGL(router_logits_mfma<false>, grid, dim3(kWave * kRtWaves), 0, st, x, N, (int)H, W_r,
-                               bias, E, logits);
+            hipLaunchKernelGGL((router_logits_mfma<false, kRtKShort>), grid, dim3(kWave * kRtWaves), 0, st, x, N, (int)H,
+                               W_r, bias, E, logits);
 #else
         if (dtype == MOE_BF16)
             hipLaunchKernelGGL(router_logits_tiled<true>, grid, dim3(kWave * kRtWaves), 0, st, x, N, (int)H, W_r,
