@@ -497,6 +497,34 @@ def main():
     torch.cuda.synchronize()
     result["layout_order"] = {"stable_us": la[0].elapsed_time(la[1]) * 1e3 / reps,
                               "arrival_us": la[1].elapsed_time(la[2]) * 1e3 / reps}
+    # Routing with the row pointers drawn in the top-K kernel, against routing followed by either layout.
+    lr = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    for timed in (False, True):
+        if timed:
+            lr[0].record()
+        for _ in range(reps):
+            hub.moe_route(st0["x"], layer.W_r, layer.bias, K, cfg.score_mode, st0["idx"], st0["w"], None, layer.route_ws)
+            hub.moe_dispatch_layout(st0["idx"], E, G, st0["cnt"], st0["off"], st0["dcnt"], st0["doff"], st0["slot"],
+                                    st0["row"], layer.layout_ws)
+        if timed:
+            lr[1].record()
+        for _ in range(reps):
+            hub.moe_route(st0["x"], layer.W_r, layer.bias, K, cfg.score_mode, st0["idx"], st0["w"], None, layer.route_ws)
+            hub.moe_dispatch_layout_arrival(st0["idx"], E, G, st0["cnt"], st0["off"], st0["dcnt"], st0["doff"],
+                                            st0["slot"], st0["row"])
+        if timed:
+            lr[2].record()
+        for _ in range(reps):
+            hub.moe_route_resolve_arrival(st0["x"], layer.W_r, layer.bias, K, G, cfg.score_mode, st0["idx"], st0["w"],
+                                          st0["cnt"], st0["off"], st0["dcnt"], st0["doff"], st0["slot"], st0["row"],
+                                          None, layer.route_ws)
+    lr[3].record()
+    hub.moe_dispatch_layout(st0["idx"], E, G, st0["cnt"], st0["off"], st0["dcnt"], st0["doff"], st0["slot"],
+                            st0["row"], layer.layout_ws)
+    torch.cuda.synchronize()
+    result["layout_order"].update({"route_then_stable_us": lr[0].elapsed_time(lr[1]) * 1e3 / reps,
+                                   "route_then_arrival_us": lr[1].elapsed_time(lr[2]) * 1e3 / reps,
+                                   "route_resolve_arrival_us": lr[2].elapsed_time(lr[3]) * 1e3 / reps})
     # Both GEMMs in one launch, the down projection's tiles starting as their rows arrive (the dependency-driven
     # form): same bits; reported beside the layer, not as `value`.
     if cfg.dtype == mi.BF16:

@@ -160,6 +160,30 @@ int moe_dispatch_layout_arrival(const int32_t *topk_idx, int64_t N, int K, int E
                                 int32_t *slot_of_row, int32_t *row_of_slot, void *stream);
 
 /*
+ * Routing and arrival-order address resolution in one call, the row pointer taken
+ * as the row is produced (Section IV-A3: a routed row draws its local row id from its
+ * region's row pointer at the moment it arrives): the top-K kernel of moe_route draws
+ * it for each of a token's K rows right after selecting their experts, so the separate
+ * rank pass of moe_dispatch_layout_arrival (and its re-read of topk_idx) is gone.
+ * Outputs are those of moe_route followed by moe_dispatch_layout_arrival: topk_idx
+ * and topk_w as moe_route gives them (bit for bit); counts, offsets and the
+ * per-destination view exact; slot_of_row / row_of_slot a valid dense packing in the
+ * order the atomics were served.  Arguments as in the two calls; ws as in moe_route
+ * (N*E*4 bytes when logits_opt is NULL).  Three launches beside the logits kernel:
+ * clear of the E row pointers, top-K with the draw, placement.  The draw is one
+ * atomic per routed row, N*K of them on E addresses; moe_dispatch_layout_arrival
+ * aggregates 1024 rows per workgroup first and is the faster form on this chip
+ * (this call exists for the comparison).
+ */
+int moe_route_resolve_arrival(const void *x, int dtype, int64_t N, int64_t H, const float *W_r,
+                              const float *bias, int E, int K, int G, int score_mode,
+                              int32_t *topk_idx, float *topk_w, float *logits_opt,
+                              int32_t *expert_counts, int32_t *expert_offsets,
+                              int32_t *dest_counts, int32_t *dest_offsets,
+                              int32_t *slot_of_row, int32_t *row_of_slot,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Dispatch, local half (Section II-A, step 2): xp[slot_of_row[n*K+k], :] = x[n, :],
  * a bitwise copy of each token row into each of its K slots.  The result is
  * expert-contiguous and therefore destination-contiguous: segment

@@ -29,6 +29,9 @@ _SIGNATURES = {
                                             _c_vp, _c_vp, _c_vp, _c_vp]),
     "moe_dispatch_layout_arrival": (_c_int, [_c_vp, _c_i64, _c_int, _c_int, _c_int, _c_vp, _c_vp, _c_vp,
                                              _c_vp, _c_vp, _c_vp, _c_vp]),
+    "moe_route_resolve_arrival": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_vp, _c_vp, _c_int, _c_int, _c_int,
+                                           _c_int, _c_vp, _c_vp, _c_vp, _c_vp, _c_vp, _c_vp, _c_vp, _c_vp, _c_vp,
+                                           _c_vp, _c_sz, _c_vp]),
     "moe_permute": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp, _c_vp]),
     "moe_grouped_ffn": (_c_int, [_c_vp, _c_int, _c_i64, _c_i64, _c_i64, _c_int, _c_vp, _c_vp, _c_vp,
                                  _c_vp, _c_vp, _c_vp, _c_sz, _c_vp]),
@@ -185,6 +188,30 @@ def moe_dispatch_layout_arrival(topk_idx, E: int, G: int, expert_counts, expert_
                                                       _ptr(expert_offsets), _ptr(dest_counts),
                                                       _ptr(dest_offsets), _ptr(slot_of_row),
                                                       _ptr(row_of_slot), _stream()))
+
+
+def moe_route_resolve_arrival(x, W_r, bias, K: int, G: int, score_mode: int, topk_idx, topk_w, expert_counts,
+                              expert_offsets, dest_counts, dest_offsets, slot_of_row, row_of_slot, logits=None,
+                              ws=None):
+    import torch
+    N, H = x.shape
+    E = W_r.shape[1]
+    _need(W_r, torch.float32, "W_r")
+    _need(topk_idx, torch.int32, "topk_idx")
+    _need(topk_w, torch.float32, "topk_w")
+    assert W_r.shape[0] == H and x.is_contiguous()
+    assert topk_idx.numel() == N * K and topk_w.numel() == N * K
+    assert logits is None or (logits.numel() == N * E and logits.dtype == torch.float32)
+    for name, t, n in (("expert_counts", expert_counts, E), ("expert_offsets", expert_offsets, E + 1),
+                       ("dest_counts", dest_counts, G), ("dest_offsets", dest_offsets, G + 1),
+                       ("slot_of_row", slot_of_row, N * K), ("row_of_slot", row_of_slot, N * K)):
+        _need(t, torch.int32, name)
+        assert t.numel() == n, name
+    wp, wb = _ws_args(ws)
+    _check(load_library().moe_route_resolve_arrival(
+        _ptr(x), _dtype_code(x), N, H, _ptr(W_r), _ptr(bias), E, K, G, score_mode, _ptr(topk_idx), _ptr(topk_w),
+        _ptr(logits), _ptr(expert_counts), _ptr(expert_offsets), _ptr(dest_counts), _ptr(dest_offsets),
+        _ptr(slot_of_row), _ptr(row_of_slot), wp, wb, _stream()))
 
 
 def moe_permute(x, K: int, slot_of_row, row_of_slot, xp):

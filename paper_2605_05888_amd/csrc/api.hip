@@ -147,6 +147,55 @@ extern "C" int moe_route(const void *x, int dtype, int64_t N, int64_t H, const f
                         static_cast<hipStream_t>(stream));
 }
 
+extern "C" int moe_route_resolve_arrival(const void *x, int dtype, int64_t N, int64_t H, const float *W_r,
+                                         const float *bias, int E, int K, int G, int score_mode,
+                                         int32_t *topk_idx, float *topk_w, float *logits_opt,
+                                         int32_t *expert_counts, int32_t *expert_offsets,
+                                         int32_t *dest_counts, int32_t *dest_offsets, int32_t *slot_of_row,
+                                         int32_t *row_of_slot, void *ws, size_t ws_bytes, void *stream)
+{
+    clear_error();
+    MOE_TRY(check_dtype(dtype));
+    MOE_TRY(check_routing_sizes(N, K, E));
+    MOE_TRY(check_rows("H", H, dtype));
+    if (K > MOE_MAX_TOPK)
+        return fail(MOE_ERR_UNSUPPORTED, "K=%d exceeds MOE_MAX_TOPK=%d", K, MOE_MAX_TOPK);
+    if (score_mode != MOE_SCORE_SOFTMAX_TOPK && score_mode != MOE_SCORE_SIGMOID_TOPK)
+        return fail(MOE_ERR_ARG, "unknown score_mode %d", score_mode);
+    if (G < 1 || E % G != 0)
+        return fail(MOE_ERR_ARG, "G must divide E (got E=%d, G=%d)", E, G);
+    if (!expert_counts || !expert_offsets || !dest_counts || !dest_offsets)
+        return fail(MOE_ERR_ARG, "count and offset outputs must not be NULL");
+    float *logits = logits_opt;
+    if (N > 0) {
+        MOE_NEED(x);
+        MOE_NEED(W_r);
+        MOE_NEED(topk_idx);
+        MOE_NEED(topk_w);
+        MOE_NEED(slot_of_row);
+        MOE_NEED(row_of_slot);
+        if (bias && !aligned16(bias))
+            return fail(MOE_ERR_ARG, "bias must be 16-byte aligned");
+        if (!logits) {
+            size_t need = (size_t)N * (size_t)E * sizeof(float);
+            if (!ws || ws_bytes < need)
+                return fail(MOE_ERR_WORKSPACE,
+                            "moe_route_resolve_arrival needs %zu workspace bytes when logits_opt is NULL (got %zu)", need,
+                            ws ? ws_bytes : (size_t)0);
+            logits = static_cast<float *>(ws);
+        }
+        if (!aligned16(logits))
+            return fail(MOE_ERR_ARG, "logits buffer must be 16-byte aligned");
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    MOE_TRY(launch_arrival_clear(expert_counts, E, st));
+    if (N > 0)
+        MOE_TRY(launch_route(x, dtype, N, H, W_r, bias, E, K, score_mode, topk_idx, topk_w, logits, st, expert_counts,
+                             slot_of_row));
+    return launch_arrival_place(topk_idx, N * (int64_t)K, E, G, expert_counts, expert_offsets, dest_counts,
+                                dest_offsets, slot_of_row, row_of_slot, st);
+}
+
 extern "C" int moe_dispatch_layout(const int32_t *topk_idx, int64_t N, int K, int E, int G,
                                    int32_t *expert_counts, int32_t *expert_offsets,
                                    int32_t *dest_counts, int32_t *dest_offsets,

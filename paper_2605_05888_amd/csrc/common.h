@@ -49,9 +49,12 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // ---- per-step launchers (each validates nothing: api.hip has done it) ----
+// row_pointer != nullptr: the top-K kernel also draws every routed row's local row id from
+// row_pointer[expert] (which must be zero on entry) into rank[n*K + k].
 int launch_route(const void *x, int dtype, int64_t N, int64_t H, const float *W_r,
                  const float *bias, int E, int K, int score_mode, int32_t *topk_idx,
-                 float *topk_w, float *logits, hipStream_t st);
+                 float *topk_w, float *logits, hipStream_t st, int32_t *row_pointer = nullptr,
+                 int32_t *rank = nullptr);
 
 size_t layout_workspace_bytes(int64_t R, int E);
 int launch_layout(const int32_t *topk_idx, int64_t R, int E, int G, int32_t *expert_counts,
@@ -63,6 +66,12 @@ int launch_layout_static(const int32_t *topk_idx, int64_t R, int E, int G, int32
 int launch_layout_arrival(const int32_t *topk_idx, int64_t R, int E, int G, int32_t *expert_counts,
                           int32_t *expert_offsets, int32_t *dest_counts, int32_t *dest_offsets,
                           int32_t *slot_of_row, int32_t *row_of_slot, hipStream_t st);
+// The two halves of the above around a rank pass done elsewhere: clear the E row pointers; turn
+// ranks (in slot_of_row) and final pointers (= counts) into offsets and slots.
+int launch_arrival_clear(int32_t *expert_counts, int E, hipStream_t st);
+int launch_arrival_place(const int32_t *topk_idx, int64_t R, int E, int G, int32_t *expert_counts,
+                         int32_t *expert_offsets, int32_t *dest_counts, int32_t *dest_offsets,
+                         int32_t *slot_of_row, int32_t *row_of_slot, hipStream_t st);
 
 int launch_permute(const void *x, int64_t row_bytes, int64_t N, int K,
                    const int32_t *slot_of_row, void *xp, hipStream_t st);

@@ -368,4 +368,22 @@ int launch_layout_arrival(const int32_t *topk_idx, int64_t R, int E, int G, int3
     return check_launch("moe_dispatch_layout_arrival");
 }
 
+int launch_arrival_clear(int32_t *expert_counts, int E, hipStream_t st)
+{
+    hipLaunchKernelGGL(layout_clear_counts, dim3((int)ceil_div(E, 256)), dim3(256), 0, st, expert_counts, E);
+    return check_launch("moe_route_resolve_arrival");
+}
+
+int launch_arrival_place(const int32_t *topk_idx, int64_t R, int E, int G, int32_t *expert_counts,
+                         int32_t *expert_offsets, int32_t *dest_counts, int32_t *dest_offsets,
+                         int32_t *slot_of_row, int32_t *row_of_slot, hipStream_t st)
+{
+    const int64_t per_block = kArrivalThreads * kArrivalRowsPerThread;
+    const int blocks = (int)ceil_div(R, per_block);
+    hipLaunchKernelGGL(arrival_place_rows, dim3(blocks > 0 ? blocks : 1), dim3(kArrivalThreads),
+                       (E + 1) * sizeof(int32_t), st, topk_idx, R, E, G, expert_counts,
+                       expert_offsets, dest_counts, dest_offsets, slot_of_row, row_of_slot);
+    return check_launch("moe_route_resolve_arrival");
+}
+
 }  // namespace moe

@@ -499,9 +499,14 @@ __device__ __forceinline__ bool better(float va, int ia, float vb, int ib)
 constexpr int kMaxPerLane = MOE_MAX_EXPERTS / kWave;
 
 // One wavefront per token.  Lane l holds experts l, l+64, ...
+// kTakeRows: every routed row also takes its local row id from its expert's row pointer as it is
+// produced (Section IV-A3: the allocation unit hands out the next free row of a region on arrival);
+// rank[n*K + k] receives it, and the pointers end up as the experts' counts.
+template <bool kTakeRows>
 __global__ __launch_bounds__(kWave *kRouteWaves) void router_topk(
     const float *__restrict__ logits, int64_t N, int E, int K, int score_mode,
-    int32_t *__restrict__ topk_idx, float *__restrict__ topk_w)
+    int32_t *__restrict__ topk_idx, float *__restrict__ topk_w, int32_t *__restrict__ row_pointer,
+    int32_t *__restrict__ rank)
 {
     const int lane = threadIdx.x % kWave;
     const int64_t n = (int64_t)blockIdx.x * kRouteWaves + threadIdx.x / kWave;
@@ -566,12 +571,14 @@ __global__ __launch_bounds__(kWave *kRouteWaves) void router_topk(
     if (lane < K) {
         topk_idx[n * K + lane] = my_pick;
         topk_w[n * K + lane] = s / sum;
+        if constexpr (kTakeRows)
+            rank[n * K + lane] = atomicAdd(&row_pointer[my_pick], 1);
     }
 }
 
 int launch_route(const void *x, int dtype, int64_t N, int64_t H, const float *W_r,
                  const float *bias, int E, int K, int score_mode, int32_t *topk_idx,
-                 float *topk_w, float *logits, hipStream_t st)
+                 float *topk_w, float *logits, hipStream_t st, int32_t *row_pointer, int32_t *rank)
 {
     const dim3 block(kWave * kRouteWaves);
     if (E % 4 == 0 && H * (int64_t)E * 4 < ((int64_t)1 << 31) && H * 8 * 4 < ((int64_t)1 << 31)) {
@@ -602,8 +609,12 @@ int launch_route(const void *x, int dtype, int64_t N, int64_t H, const float *W_
             hipLaunchKernelGGL(router_logits<false>, grid1, block, 0, st, x, N, H, W_r, bias, E, logits);
     }
     const dim3 grid2((unsigned)ceil_div(N, kRouteWaves));
-    hipLaunchKernelGGL(router_topk, grid2, block, 0, st, logits, N, E, K, score_mode, topk_idx,
-                       topk_w);
+    if (row_pointer)
+        hipLaunchKernelGGL(router_topk<true>, grid2, block, 0, st, logits, N, E, K, score_mode, topk_idx, topk_w,
+                           row_pointer, rank);
+    else
+        hipLaunchKernelGGL(router_topk<false>, grid2, block, 0, st, logits, N, E, K, score_mode, topk_idx, topk_w,
+                           (int32_t *)nullptr, (int32_t *)nullptr);
     return check_launch("moe_route");
 }
 

@@ -65,6 +65,27 @@ def gpu_layout_arrival(idx, E, G):
     return out
 
 
+def gpu_route_resolve_arrival(x, W_r, bias, K, G, score_mode):
+    """Routing and arrival-order address resolution in one call: (idx, w, logits, layout dict)."""
+    N, H = x.shape
+    E = W_r.shape[1]
+    R = N * K
+    idx = torch.full((N, K), -1, dtype=torch.int32, device=DEV)
+    w = torch.zeros((N, K), dtype=torch.float32, device=DEV)
+    logits = torch.zeros((N, E), dtype=torch.float32, device=DEV)
+    out = dict(
+        expert_counts=torch.full((E,), -7, dtype=torch.int32, device=DEV),
+        expert_offsets=torch.full((E + 1,), -7, dtype=torch.int32, device=DEV),
+        dest_counts=torch.full((G,), -7, dtype=torch.int32, device=DEV),
+        dest_offsets=torch.full((G + 1,), -7, dtype=torch.int32, device=DEV),
+        slot_of_row=torch.full((R,), -7, dtype=torch.int32, device=DEV),
+        row_of_slot=torch.full((R,), -7, dtype=torch.int32, device=DEV))
+    hub.moe_route_resolve_arrival(x, W_r, bias, K, G, score_mode, idx, w, out["expert_counts"], out["expert_offsets"],
+                                  out["dest_counts"], out["dest_offsets"], out["slot_of_row"], out["row_of_slot"],
+                                  logits)
+    return idx, w, logits, out
+
+
 def gpu_permute(x, K, lay):
     N, H = x.shape
     xp = torch.zeros((N * K, H), dtype=x.dtype, device=DEV)

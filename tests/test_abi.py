@@ -20,7 +20,7 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert set(names) == {"moe_last_error", "moe_workspace_bytes", "moe_route", "moe_dispatch_layout",
-                          "moe_dispatch_layout_arrival", "moe_dispatch_layout_static",
+                          "moe_dispatch_layout_arrival", "moe_dispatch_layout_static", "moe_route_resolve_arrival",
                           "moe_permute", "moe_grouped_ffn", "moe_combine",
                           "moe_ffn_schedule", "moe_ffn_gate_up", "moe_ffn_gate_up_gather", "moe_ffn_down",
                           "moe_ffn_down_combine", "moe_ffn_status", "moe_ffn_gate_up_down"}

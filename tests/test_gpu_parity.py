@@ -128,6 +128,46 @@ def test_arrival_order_layout_unique_parts_exact_and_slots_valid(G, N, E, K, Gd,
         check_layout_is_valid(idx, E, Gd, got)
 
 
+@pytest.mark.parametrize("name", list(SMALL))
+def test_route_with_rows_taken_on_arrival(G, name):
+    """moe_route_resolve_arrival (the row pointer drawn in the top-K kernel, as the row is produced): routing
+    outputs bit for bit those of the oracle, counts / offsets / destinations exact, slot maps a valid dense packing;
+    twice, the second call over used buffers."""
+    import moe_inputs.device as mid
+    from layout_checks import check_layout_is_valid
+    cfg = SMALL[name]
+    _say("route + arrival-order resolution", cfg)
+    x, Wr = mi.host_tensor(cfg, mi.STREAM_X), mi.host_tensor(cfg, mi.STREAM_W_ROUTER)
+    bias = mi.router_bias(cfg)
+    o_idx, o_w, o_lg = oracle.route(x, Wr, bias, cfg.K, cfg.score_mode)
+    want = oracle.layout(o_idx, cfg.E, cfg.G)
+    dbias = None if bias is None else mid.to_device(bias)
+    dx, dWr = mid.to_device(x), mid.to_device(Wr)
+    for _ in range(2):
+        idx, w, lg, lay = G.gpu_route_resolve_arrival(dx, dWr, dbias, cfg.K, cfg.G, cfg.score_mode)
+        assert np.array_equal(G.host(lg).view(np.uint32), o_lg.view(np.uint32))
+        assert np.array_equal(G.host(idx), o_idx)
+        assert np.max(np.abs(G.host(w).astype(np.float64) - o_w)) <= 2e-6
+        got = {k: G.host(v) for k, v in lay.items()}
+        for k in ("expert_counts", "expert_offsets", "dest_counts", "dest_offsets"):
+            assert np.array_equal(got[k], want[k]), k
+        check_layout_is_valid(o_idx, cfg.E, cfg.G, got)
+
+
+def test_route_with_rows_taken_on_arrival_no_tokens(G):
+    import torch
+    import paper_2605_05888_amd as hub
+    E, Gd, K = 8, 2, 2
+    z = lambda n, v=-7: torch.full((n,), v, dtype=torch.int32, device="cuda:0")
+    cnt, off, dc, do = z(E), z(E + 1), z(Gd), z(Gd + 1)
+    x = torch.zeros((0, 64), dtype=torch.bfloat16, device="cuda:0")
+    Wr = torch.zeros((64, E), dtype=torch.float32, device="cuda:0")
+    hub.moe_route_resolve_arrival(x, Wr, None, K, Gd, hub.SCORE_SOFTMAX_TOPK, z(0).reshape(0, K),
+                                  torch.zeros((0, K), dtype=torch.float32, device="cuda:0"), cnt, off, dc, do, z(0), z(0))
+    torch.cuda.synchronize()
+    assert not cnt.any() and not off.any() and not dc.any() and not do.any()
+
+
 def test_arrival_order_layout_all_rows_to_one_expert(G):
     import moe_inputs.device as mid
     from layout_checks import check_layout_is_valid
