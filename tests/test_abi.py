@@ -69,6 +69,15 @@ ALIGNED = 0x1000   # a fake, well-aligned, never-dereferenced pointer: every cas
                                              ALIGNED, None), -1, "divide"),
     (lambda L: L.moe_dispatch_layout_arrival(ALIGNED, 4, 2, 8, 2, ALIGNED, ALIGNED, ALIGNED, ALIGNED, None,
                                              ALIGNED, None), -1, "NULL"),
+    (lambda L: L.moe_route_resolve_arrival(ALIGNED, hub.BF16, 4, 64, ALIGNED, None, 8, 2, 3, 0, ALIGNED, ALIGNED,
+                                           ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED, None, 0, None),
+     -1, "divide"),
+    (lambda L: L.moe_route_resolve_arrival(ALIGNED, hub.BF16, 4, 64, ALIGNED, None, 8, 2, 2, 0, ALIGNED, ALIGNED,
+                                           None, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED, None, 0, None),
+     -3, "workspace"),
+    (lambda L: L.moe_route_resolve_arrival(ALIGNED, hub.BF16, 4, 64, ALIGNED, None, 8, 2, 2, 0, ALIGNED, ALIGNED,
+                                           ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED, None, ALIGNED, None, 0, None),
+     -1, "NULL"),
     (lambda L: L.moe_grouped_ffn(ALIGNED, hub.BF16, 64, 64, 64, 0, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED,
                                  ALIGNED, 1 << 30, None), -1, "E_local"),
     (lambda L: L.moe_grouped_ffn(ALIGNED, hub.BF16, 64, 64, 64, 2, ALIGNED, ALIGNED, ALIGNED, ALIGNED, ALIGNED,
