@@ -13,6 +13,9 @@
 namespace moe {
 
 constexpr int kTokensPerBlock = 4; // one wavefront each
+#ifndef MOE_COMBINE_U
+#define MOE_COMBINE_U 4 // 16-byte chunks of a row a lane gathers at a time (per k), at most
+#endif
 
 // Value of lane k (k wave-uniform) whatever lanes are active: the chunk loops below run a different
 // number of times per lane, and a cross-lane read that honours the execution mask (__shfl) returns 0
@@ -115,8 +118,14 @@ __global__ __launch_bounds__(kWave *kTokensPerBlock) void combine_rows(
         }
     };
     int c = lane;
+#if MOE_COMBINE_U == 8
+    for (; c + 7 * kWave < chunks; c += 8 * kWave)
+        rows_of(std::integral_constant<int, 8>{}, c);
+#endif
     for (; c + 3 * kWave < chunks; c += 4 * kWave)
         rows_of(std::integral_constant<int, 4>{}, c);
+    for (; c + kWave < chunks; c += 2 * kWave)
+        rows_of(std::integral_constant<int, 2>{}, c);
     for (; c < chunks; c += kWave)
         rows_of(std::integral_constant<int, 1>{}, c);
 }
