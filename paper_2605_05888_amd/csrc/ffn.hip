@@ -587,8 +587,8 @@ int ffn_status(int64_t M, int64_t H, int64_t F, int E_local, const void *ws, hip
                                                         : fail(MOE_ERR_LAUNCH, "moe_ffn_status: copy failed");
     for (int g = 0; g < 2; ++g) {
         if (err[g] == kNoScheduleError)
-            return fail(MOE_ERR_STATE, "GEMM%d ran over a workspace that moe_ffn_schedule had not filled for M=%lld",
-                        g + 1, (long long)M);
+            return fail(MOE_ERR_STATE, "GEMM%d ran over a workspace that moe_ffn_schedule had not filled for M=%lld "
+                                       "(and this H, F, E_local)", g + 1, (long long)M);
         if (err[g] == kDependencyTimeout)
             return fail(MOE_ERR_STATE, "GEMM%d gave up waiting for rows of the first GEMM (poll limit reached); "
                                        "its output is incomplete", g + 1);
